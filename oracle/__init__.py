@@ -1,0 +1,164 @@
+"""CPU oracle for DistAttention decode attention: TEST INFRASTRUCTURE ONLY.
+
+A thin ctypes loader over ``oracle/da_oracle.c`` (fp64, plain loops).  Only the
+tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import this
+package; the product path never does.  It shares nothing with the HIP library.
+
+Arrays are numpy: fp32 data as ``float32``, bf16 data as ``uint16`` holding the
+raw bit patterns.  Pools are addressed as
+``pool[pb*stride_block + g*stride_head + slot*stride_token + c]`` in elements.
+
+  attention()        Section 4, Eq. 1 (plain definition, two passes)
+  micro_attention()  Section 4, m_j / e_j equation and Eq. 2
+  aggregate()        Section 4, m_g / e_g equation and Eq. 3
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "da_oracle.c")
+_LIB = os.path.join(_HERE, "libda_oracle.so")
+
+F32, BF16 = 0, 1
+
+
+def build(force=False):
+    """Compile the oracle with gcc (plain -O2, OpenMP only to spread (request, head) pairs)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+class _Problem(ctypes.Structure):
+    _fields_ = [
+        ("q", ctypes.c_void_p), ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p),
+        ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
+        ("q_dtype", ctypes.c_int), ("kv_dtype", ctypes.c_int),
+        ("B", ctypes.c_int), ("Hq", ctypes.c_int), ("Hkv", ctypes.c_int), ("d", ctypes.c_int),
+        ("T", ctypes.c_int), ("max_blocks", ctypes.c_int),
+        ("stride_block", ctypes.c_int64), ("stride_head", ctypes.c_int64),
+        ("stride_token", ctypes.c_int64),
+        ("scale", ctypes.c_double),
+    ]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_attention.restype = ctypes.c_int
+        _lib.oracle_attention.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_int64,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        _lib.oracle_micro_attention.restype = ctypes.c_int
+        _lib.oracle_micro_attention.argtypes = [ctypes.POINTER(_Problem), ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        _lib.oracle_aggregate.restype = ctypes.c_int
+        _lib.oracle_aggregate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_void_p]
+    return _lib
+
+
+def _dtype_code(a):
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError("oracle takes float32 or uint16 (bf16 bits), got %s" % a.dtype)
+
+
+def _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, strides, keep):
+    B, Hq, d = q.shape
+    if k_pool.ndim != 4 or v_pool.shape != k_pool.shape:
+        raise ValueError("pools must be [num_phys_blocks][Hkv][T][d]")
+    _, Hkv, T, dd = k_pool.shape
+    if dd != d or T != block_tokens:
+        raise ValueError("pool shape does not match q / block_tokens")
+    if strides is None:
+        strides = (Hkv * T * d, T * d, d)
+    q = np.ascontiguousarray(q)
+    k_pool = np.ascontiguousarray(k_pool)
+    v_pool = np.ascontiguousarray(v_pool)
+    block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+    seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    if _dtype_code(k_pool) != _dtype_code(v_pool):
+        raise TypeError("K and V pools must share a dtype")
+    keep.extend([q, k_pool, v_pool, block_table, seq_lens])
+    p = _Problem()
+    p.q, p.k_pool, p.v_pool = q.ctypes.data, k_pool.ctypes.data, v_pool.ctypes.data
+    p.block_table, p.seq_lens = block_table.ctypes.data, seq_lens.ctypes.data
+    p.q_dtype, p.kv_dtype = _dtype_code(q), _dtype_code(k_pool)
+    p.B, p.Hq, p.Hkv, p.d, p.T = B, Hq, Hkv, d, T
+    p.max_blocks = block_table.shape[1]
+    p.stride_block, p.stride_head, p.stride_token = strides
+    p.scale = float(scale)
+    return p
+
+
+def attention(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale,
+              pairs=None, strides=None, n_threads=1):
+    """Eq. 1.  Returns (out, lse) in fp64: [B][Hq][d], [B][Hq]; or [n][d], [n] for ``pairs`` (n x 2: r, h)."""
+    keep = []
+    p = _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, strides, keep)
+    if pairs is None:
+        n = p.B * p.Hq
+        pairs_ptr = None
+    else:
+        pairs = np.ascontiguousarray(pairs, dtype=np.int32).reshape(-1, 2)
+        n = pairs.shape[0]
+        pairs_ptr = pairs.ctypes.data
+    out = np.empty((n, p.d), dtype=np.float64)
+    lse = np.empty((n,), dtype=np.float64)
+    rc = _load().oracle_attention(ctypes.byref(p), pairs_ptr, n, out.ctypes.data, lse.ctypes.data, n_threads)
+    if rc != 0:
+        raise ValueError("oracle_attention rejected its arguments")
+    if pairs is None:
+        return out.reshape(p.B, p.Hq, p.d), lse.reshape(p.B, p.Hq)
+    return out, lse
+
+
+def micro_attention(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, bounds,
+                    strides=None, n_threads=1):
+    """Eq. 2 over caller-chosen partitions.
+
+    ``bounds[r]`` is the increasing list of token boundaries of request r
+    (len = nparts[r] + 1).  Returns (MA [rows][d], m [rows], e [rows], nparts [B]) with
+    row(r, h, j) = Hq * sum_{r'<r} nparts[r'] + h * nparts[r] + j.
+    """
+    keep = []
+    p = _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, strides, keep)
+    nparts = np.array([len(b) - 1 for b in bounds], dtype=np.int32)
+    flat = np.ascontiguousarray(np.concatenate([np.asarray(b, dtype=np.int64) for b in bounds]))
+    rows = int(nparts.sum()) * p.Hq
+    MA = np.empty((rows, p.d), dtype=np.float64)
+    m = np.empty((rows,), dtype=np.float64)
+    e = np.empty((rows,), dtype=np.float64)
+    rc = _load().oracle_micro_attention(ctypes.byref(p), nparts.ctypes.data, flat.ctypes.data,
+                                        MA.ctypes.data, m.ctypes.data, e.ctypes.data, n_threads)
+    if rc != 0:
+        raise ValueError("oracle_micro_attention rejected its arguments")
+    return MA, m, e, nparts
+
+
+def aggregate(MA, m, e, nparts, num_q_heads):
+    """Eq. 3.  Returns (out [B][Hq][d], lse [B][Hq]) in fp64."""
+    MA = np.ascontiguousarray(MA, dtype=np.float64)
+    m = np.ascontiguousarray(m, dtype=np.float64)
+    e = np.ascontiguousarray(e, dtype=np.float64)
+    nparts = np.ascontiguousarray(nparts, dtype=np.int32)
+    B, d = nparts.shape[0], MA.shape[1]
+    out = np.empty((B, num_q_heads, d), dtype=np.float64)
+    lse = np.empty((B, num_q_heads), dtype=np.float64)
+    rc = _load().oracle_aggregate(B, num_q_heads, d, nparts.ctypes.data, MA.ctypes.data, m.ctypes.data,
+                                  e.ctypes.data, out.ctypes.data, lse.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_aggregate rejected its arguments")
+    return out, lse

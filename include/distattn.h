@@ -1,0 +1,187 @@
+/*
+ * distattn.h - C ABI of the DistAttention decode hot path for AMD MI355X (gfx950).
+ *
+ * DistAttention (Infinite-LLM, Section 4) cuts the KV cache of every request
+ * along the sequence into fixed-size blocks.  A run of blocks is attended to by
+ * an independent MicroAttention that returns an un-normalised partial output
+ * MA_j with its local score maximum m_j and exp-sum e_j (Section 4, Eq. 2 and
+ * the m_j / e_j equation above it); an aggregation step (Section 4, Eq. 3 and
+ * the m_g / e_g equation above it) turns the partials of one query into exactly
+ * softmax(scale * q K^T) V (Section 4, Eq. 1).
+ *
+ * Scope: decode (one query token per request), MHA / MQA / GQA (Section 3),
+ * one GPU.  Everything runs in hand-written HIP kernels; there is no CPU
+ * fallback.  All entry points return a da_status; none aborts, throws or prints.
+ *
+ * Memory: every tensor pointer below is DEVICE memory owned by the caller
+ * unless its name ends in _host.  The library allocates device memory only
+ * inside da_plan_create (a few small tables) and frees it in da_plan_destroy.
+ * All kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ * the default stream); no entry point except da_plan_error synchronises.
+ *
+ * Layouts (element = one kv_dtype / q_dtype value; strides in elements):
+ *   q            [batch][num_q_heads][head_dim], contiguous
+ *   k_pool,v_pool element (pb, g, s, c) at pb*kv_block_stride + g*kv_head_stride
+ *                + s*kv_token_stride + c;  pb < num_phys_blocks is a physical
+ *                block, g a kv-head, s < block_tokens a slot, c < head_dim.
+ *                A (token, head) row of head_dim elements is contiguous and must
+ *                start on a 16-byte boundary.
+ *   block_table  int32 [batch][max_blocks_per_seq]; logical token i of request r
+ *                lives in physical block block_table[r][i / block_tokens] at slot
+ *                i % block_tokens.  Entries past ceil(seq_len / block_tokens) are
+ *                never read.
+ *   seq_lens     int32 [batch]; tokens i >= seq_lens[r] never influence a result
+ *                (their slots may hold anything, NaN included).
+ *   out          fp32 [batch][num_q_heads][head_dim]
+ *   lse          fp32 [batch][num_q_heads], m_g + ln(e_g)  (optional)
+ *   part_o       fp32 [num_partials][head_dim]   MA_j, un-normalised (Eq. 2)
+ *   part_m       fp32 [num_partials]             m_j (natural-log units of scale*q.k)
+ *   part_e       fp32 [num_partials]             e_j
+ *     A partial row belongs to one (request r, q-head h, split j):
+ *       row(r, h, j) = num_q_heads * sum_{r' < r} nsplits[r'] + h * nsplits[r] + j
+ *     so the rows of one (r, h) are contiguous and can be aggregated in any
+ *     order or grouping.
+ *
+ * Semantics: q-head h reads kv-head h / (num_q_heads / num_kv_heads).  The
+ * query attends to all seq_lens[r] cached tokens (no causal mask: decode).  An
+ * empty request yields out = 0 and lse = -inf; an empty split yields m = -inf,
+ * e = 0, MA = 0 and has weight 0 in the aggregation.
+ */
+#ifndef DISTATTN_H
+#define DISTATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DA_OK = 0,
+    DA_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, Hq % Hkv != 0, misaligned stride ... */
+    DA_ERR_UNSUPPORTED = 2, /* head_dim != 128, block_tokens % 16 != 0, unknown dtype, group > 64 */
+    DA_ERR_WORKSPACE = 3,   /* workspace smaller than da_workspace_bytes() */
+    DA_ERR_HIP = 4          /* a HIP runtime call failed (no device, launch failure, out of memory) */
+} da_status;
+
+typedef enum { DA_F32 = 0, DA_BF16 = 1 } da_dtype;
+
+/* MicroAttention kernel families (da_tuning.kernel). */
+typedef enum {
+    DA_KERNEL_AUTO = 0, /* VALU for group size 1 and for fp32 K/V, MFMA otherwise */
+    DA_KERNEL_VALU = 1, /* fp32 vector ALU dot products, wavefront (DPP) reductions */
+    DA_KERNEL_MFMA = 2  /* bf16 matrix-core products for the (q-head group) x (KV tile) contractions */
+} da_kernel;
+
+typedef struct {
+    int32_t batch;              /* B  >= 1 */
+    int32_t num_q_heads;        /* Hq >= 1 */
+    int32_t num_kv_heads;       /* Hkv >= 1, divides Hq */
+    int32_t head_dim;           /* 128 */
+    int32_t block_tokens;       /* T: tokens per KV block, a positive multiple of 16 */
+    int32_t max_blocks_per_seq; /* row length of block_table, >= 1 */
+    int32_t num_phys_blocks;    /* blocks in each pool; table entries outside [0, n) are rejected in-kernel */
+    int32_t kv_dtype;           /* da_dtype of k_pool and v_pool */
+    int32_t q_dtype;            /* da_dtype of q */
+    float scale;                /* score scale, e.g. 1/sqrt(head_dim); finite */
+    int64_t kv_block_stride;    /* elements between physical blocks */
+    int64_t kv_head_stride;     /* elements between kv-heads inside a block */
+    int64_t kv_token_stride;    /* elements between slots; >= head_dim */
+} da_problem;
+
+/* Scheduling knobs; a NULL da_tuning* or a zero field means "choose". */
+typedef struct {
+    int32_t blocks_per_split; /* KV blocks per MicroAttention; 1 = one partial per block as in Section 4 */
+    int32_t num_cus;          /* compute units to fill; 0 = ask the device (256 on MI355X) */
+    int32_t kernel;           /* da_kernel */
+} da_tuning;
+
+typedef struct da_plan da_plan; /* opaque: split schedule of one batch + its small device tables */
+
+/*
+ * Work scheduling (host).  Section 5.3, Eq. 5 prices attention by total KV
+ * length, not batch size; Section 3 allows partitions of any length.  The
+ * plan therefore cuts every request's blocks into nsplits[r] near-equal runs
+ * ("splits") sized so that the (split, kv-head) work items keep every compute
+ * unit busy, from one short request to one 2M-token request.
+ *
+ * da_plan_schedule: pure host arithmetic, no HIP call.  Writes nsplits[r]
+ *   (>= 1; 1 for an empty request) into nsplits_host[batch] and the processing
+ *   order (request ids, longest first) into order_host[batch]; either may be
+ *   NULL.  *num_items = work items of the MicroAttention launch, *num_partials
+ *   = rows of part_*, *kernel = the da_kernel chosen.
+ * da_plan_create: the same schedule, plus its device tables.  seq_lens_host is
+ *   read during the call and not retained.  Destroy with da_plan_destroy.
+ * da_plan_update: re-plan the same problem for new lengths in place (no
+ *   allocation unless the batch grew beyond the created capacity, which is an
+ *   error).  Ordered on `stream` after earlier launches that used the plan.
+ * The lengths given here must equal the device seq_lens passed to the launch
+ * calls; the device values decide which tokens are read, the host values only
+ * how the work is cut.
+ * Errors: DA_ERR_INVALID_ARG / DA_ERR_UNSUPPORTED from validation (before any
+ * HIP call), DA_ERR_HIP if the device tables cannot be made.
+ */
+da_status da_plan_schedule(const da_problem *problem, const int32_t *seq_lens_host, const da_tuning *tuning,
+                           int32_t *nsplits_host, int32_t *order_host, int64_t *num_items,
+                           int64_t *num_partials, int32_t *kernel);
+da_status da_plan_create(const da_problem *problem, const int32_t *seq_lens_host, const da_tuning *tuning,
+                         void *stream, da_plan **plan);
+da_status da_plan_update(da_plan *plan, const int32_t *seq_lens_host, void *stream);
+da_status da_plan_destroy(da_plan *plan);
+
+/* Rows of part_o / part_m / part_e for this plan. */
+da_status da_plan_num_partials(const da_plan *plan, int64_t *num_partials);
+/* Split j of request r covers logical blocks [*first_block, *first_block + *num_blocks). */
+da_status da_plan_split(const da_plan *plan, int32_t r, int32_t j, int32_t *first_block, int32_t *num_blocks);
+/* nsplits[r]. */
+da_status da_plan_nsplits(const da_plan *plan, int32_t r, int32_t *nsplits);
+/* Bytes of device workspace da_attention needs (the three part_* arrays, 256-byte aligned each). */
+da_status da_workspace_bytes(const da_plan *plan, size_t *bytes);
+/*
+ * Blocking: waits for `stream`, then reports in *flags whether any kernel that
+ * used this plan met a block_table entry outside [0, num_phys_blocks) (bit 0).
+ * Such a block is skipped (its tokens contribute nothing) instead of being
+ * read.  Clears the flag.
+ */
+da_status da_plan_error(da_plan *plan, void *stream, int32_t *flags);
+
+/*
+ * MicroAttention (Section 4, m_j / e_j equation and Eq. 2): for every split j
+ * of every (request, kv-head) and each q-head h of that kv-head's group, over
+ * the split's valid tokens i:
+ *   s_i = scale * q_h . k_i,  m_j = max_i s_i,  e_j = sum_i exp(s_i - m_j),
+ *   MA_j = sum_i exp(s_i - m_j) v_i
+ * written to row(r, h, j) of part_o / part_m / part_e.  K and V are read once
+ * per kv-head; all q-heads of a group share that read.
+ */
+da_status da_partial(const da_plan *plan, const void *q, const void *k_pool, const void *v_pool,
+                     const int32_t *block_table, const int32_t *seq_lens,
+                     float *part_o, float *part_m, float *part_e, void *stream);
+
+/*
+ * Aggregation (Section 4, m_g / e_g equation and Eq. 3): per (request, q-head)
+ *   m_g = max_j m_j,  e_g = sum_j e_j exp(m_j - m_g),
+ *   out = sum_j MA_j exp(m_j - m_g) / e_g,   lse = m_g + ln e_g  (lse may be NULL).
+ * The partials may come from da_partial or from anywhere else that follows the
+ * row convention (e.g. another device's MicroAttention).
+ */
+da_status da_combine(const da_plan *plan, const float *part_o, const float *part_m, const float *part_e,
+                     float *out, float *lse, void *stream);
+
+/*
+ * Fused convenience call: MicroAttention into `workspace`, then aggregation,
+ * on one stream = Section 4, Eq. 1.  A request with a single split is
+ * normalised inside the MicroAttention kernel and skips the aggregation.
+ * workspace_bytes must be >= da_workspace_bytes(); workspace 256-byte aligned.
+ */
+da_status da_attention(const da_plan *plan, const void *q, const void *k_pool, const void *v_pool,
+                       const int32_t *block_table, const int32_t *seq_lens, float *out, float *lse,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+const char *da_status_string(da_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DISTATTN_H */

@@ -1,0 +1,355 @@
+// C ABI of the DistAttention decode library: argument checks, plan objects, kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+
+#include "../../include/distattn.h"
+#include "kernel_params.h"
+#include "schedule.h"
+
+namespace da {
+hipError_t launch_micro_attention_valu(const MicroParams &p, bool kv_bf16, int64_t num_items, hipStream_t stream);
+hipError_t launch_combine(const CombineParams &p, hipStream_t stream);
+}  // namespace da
+
+namespace {
+
+constexpr int kRing = 4;  // pinned staging slots for table uploads
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct TableLayout {
+    size_t order, item_prefix, nsplits, row_base, err, total;
+    explicit TableLayout(int B)
+    {
+        size_t off = 0;
+        order = off;       off = align_up(off + sizeof(int32_t) * B, 16);
+        item_prefix = off; off = align_up(off + sizeof(int32_t) * (B + 1), 16);
+        nsplits = off;     off = align_up(off + sizeof(int32_t) * B, 16);
+        row_base = off;    off = align_up(off + sizeof(int64_t) * B, 16);
+        total = off;  // uploaded part
+        err = off;    off = align_up(off + sizeof(int32_t), 16);
+    }
+};
+
+}  // namespace
+
+struct da_plan {
+    da_problem problem;
+    da_tuning tuning;
+    int32_t num_cus;
+    int device;
+    da::Schedule sched;
+    char *dev = nullptr;       // device tables (+ error flag at layout.err)
+    size_t dev_bytes = 0;
+    char *stage[kRing] = {};   // pinned host staging
+    hipEvent_t ev[kRing] = {};
+    bool ev_pending[kRing] = {};
+    int ring = 0;
+};
+
+namespace {
+
+da_status upload(da_plan *pl, hipStream_t stream)
+{
+    const int B = pl->problem.batch;
+    const TableLayout lay(B);
+    const int slot = pl->ring;
+    pl->ring = (pl->ring + 1) % kRing;
+    if (pl->ev_pending[slot]) {
+        if (hipEventSynchronize(pl->ev[slot]) != hipSuccess) return DA_ERR_HIP;
+        pl->ev_pending[slot] = false;
+    }
+    char *h = pl->stage[slot];
+    std::memcpy(h + lay.order, pl->sched.order.data(), sizeof(int32_t) * B);
+    std::memcpy(h + lay.item_prefix, pl->sched.item_prefix.data(), sizeof(int32_t) * (B + 1));
+    std::memcpy(h + lay.nsplits, pl->sched.nsplits.data(), sizeof(int32_t) * B);
+    std::memcpy(h + lay.row_base, pl->sched.row_base.data(), sizeof(int64_t) * B);
+    if (hipMemcpyAsync(pl->dev, h, lay.total, hipMemcpyHostToDevice, stream) != hipSuccess) return DA_ERR_HIP;
+    if (hipEventRecord(pl->ev[slot], stream) != hipSuccess) return DA_ERR_HIP;
+    pl->ev_pending[slot] = true;
+    return DA_OK;
+}
+
+void fill_micro(const da_plan *pl, da::MicroParams &mp)
+{
+    const da_problem &p = pl->problem;
+    const TableLayout lay(p.batch);
+    mp.order = (const int32_t *)(pl->dev + lay.order);
+    mp.item_prefix = (const int32_t *)(pl->dev + lay.item_prefix);
+    mp.nsplits = (const int32_t *)(pl->dev + lay.nsplits);
+    mp.row_base = (const int64_t *)(pl->dev + lay.row_base);
+    mp.err_flag = (int32_t *)(pl->dev + lay.err);
+    mp.B = p.batch;
+    mp.Hq = p.num_q_heads;
+    mp.Hkv = p.num_kv_heads;
+    mp.G = p.num_q_heads / p.num_kv_heads;
+    mp.T = p.block_tokens;
+    mp.max_blocks = p.max_blocks_per_seq;
+    mp.num_phys = p.num_phys_blocks;
+    mp.head_tile = pl->sched.head_tile;
+    mp.head_tiles = pl->sched.head_tiles;
+    mp.q_bf16 = p.q_dtype == DA_BF16;
+    mp.stride_block = p.kv_block_stride;
+    mp.stride_head = p.kv_head_stride;
+    mp.stride_token = p.kv_token_stride;
+    mp.scale_log2e = p.scale * 1.4426950408889634f;
+}
+
+da_status launch_micro(const da_plan *pl, const da::MicroParams &mp, hipStream_t stream)
+{
+    hipError_t e = hipErrorInvalidValue;
+    if (pl->sched.kernel == DA_KERNEL_VALU)
+        e = da::launch_micro_attention_valu(mp, pl->problem.kv_dtype == DA_BF16, pl->sched.num_items, stream);
+    return e == hipSuccess ? DA_OK : DA_ERR_HIP;
+}
+
+void fill_combine(const da_plan *pl, da::CombineParams &cp)
+{
+    const TableLayout lay(pl->problem.batch);
+    cp.nsplits = (const int32_t *)(pl->dev + lay.nsplits);
+    cp.row_base = (const int64_t *)(pl->dev + lay.row_base);
+    cp.B = pl->problem.batch;
+    cp.Hq = pl->problem.num_q_heads;
+    cp.col_slices = ((int64_t)cp.B * cp.Hq < 1024) ? 4 : 1;
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char *da_status_string(da_status s)
+{
+    switch (s) {
+    case DA_OK: return "ok";
+    case DA_ERR_INVALID_ARG: return "invalid argument";
+    case DA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case DA_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case DA_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+da_status da_plan_schedule(const da_problem *problem, const int32_t *seq_lens_host, const da_tuning *tuning,
+                           int32_t *nsplits_host, int32_t *order_host, int64_t *num_items, int64_t *num_partials,
+                           int32_t *kernel)
+{
+    if (!problem || !seq_lens_host) return DA_ERR_INVALID_ARG;
+    da_tuning t = {0, 0, 0};
+    if (tuning) t = *tuning;
+    if (t.num_cus < 0) return DA_ERR_INVALID_ARG;
+    da::Schedule s;
+    da_status st = da::make_schedule(*problem, seq_lens_host, t, t.num_cus > 0 ? t.num_cus : 256, s);
+    if (st != DA_OK) return st;
+    if (nsplits_host) std::memcpy(nsplits_host, s.nsplits.data(), sizeof(int32_t) * problem->batch);
+    if (order_host) std::memcpy(order_host, s.order.data(), sizeof(int32_t) * problem->batch);
+    if (num_items) *num_items = s.num_items;
+    if (num_partials) *num_partials = s.num_partials;
+    if (kernel) *kernel = s.kernel;
+    return DA_OK;
+}
+
+da_status da_plan_create(const da_problem *problem, const int32_t *seq_lens_host, const da_tuning *tuning,
+                         void *stream, da_plan **plan)
+{
+    if (!plan) return DA_ERR_INVALID_ARG;
+    *plan = nullptr;
+    if (!problem || !seq_lens_host) return DA_ERR_INVALID_ARG;
+    da_status st = da::validate_problem(*problem);
+    if (st != DA_OK) return st;
+    da_tuning t = {0, 0, 0};
+    if (tuning) t = *tuning;
+    if (t.num_cus < 0) return DA_ERR_INVALID_ARG;
+
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return DA_ERR_HIP;
+    int cus = t.num_cus;
+    if (cus == 0) {
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1)
+            return DA_ERR_HIP;
+    }
+
+    da_plan *pl = new (std::nothrow) da_plan();
+    if (!pl) return DA_ERR_HIP;
+    pl->problem = *problem;
+    pl->tuning = t;
+    pl->num_cus = cus;
+    pl->device = device;
+    st = da::make_schedule(pl->problem, seq_lens_host, t, cus, pl->sched);
+    if (st != DA_OK) {
+        delete pl;
+        return st;
+    }
+    const TableLayout lay(problem->batch);
+    pl->dev_bytes = lay.err + 16;
+    bool ok = hipMalloc((void **)&pl->dev, pl->dev_bytes) == hipSuccess;
+    for (int i = 0; ok && i < kRing; ++i) {
+        ok = hipHostMalloc((void **)&pl->stage[i], lay.total, hipHostMallocDefault) == hipSuccess &&
+             hipEventCreateWithFlags(&pl->ev[i], hipEventDisableTiming) == hipSuccess;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    ok = ok && hipMemsetAsync(pl->dev + lay.err, 0, 16, s) == hipSuccess;
+    if (ok) ok = upload(pl, s) == DA_OK;
+    if (!ok) {
+        da_plan_destroy(pl);
+        return DA_ERR_HIP;
+    }
+    *plan = pl;
+    return DA_OK;
+}
+
+da_status da_plan_update(da_plan *pl, const int32_t *seq_lens_host, void *stream)
+{
+    if (!pl || !seq_lens_host) return DA_ERR_INVALID_ARG;
+    da::Schedule s;
+    da_status st = da::make_schedule(pl->problem, seq_lens_host, pl->tuning, pl->num_cus, s);
+    if (st != DA_OK) return st;
+    pl->sched = std::move(s);
+    return upload(pl, (hipStream_t)stream);
+}
+
+da_status da_plan_destroy(da_plan *pl)
+{
+    if (!pl) return DA_OK;
+    for (int i = 0; i < kRing; ++i) {
+        if (pl->ev_pending[i]) (void)hipEventSynchronize(pl->ev[i]);
+        if (pl->ev[i]) (void)hipEventDestroy(pl->ev[i]);
+        if (pl->stage[i]) (void)hipHostFree(pl->stage[i]);
+    }
+    if (pl->dev) (void)hipFree(pl->dev);
+    delete pl;
+    return DA_OK;
+}
+
+da_status da_plan_num_partials(const da_plan *pl, int64_t *n)
+{
+    if (!pl || !n) return DA_ERR_INVALID_ARG;
+    *n = pl->sched.num_partials;
+    return DA_OK;
+}
+
+da_status da_plan_nsplits(const da_plan *pl, int32_t r, int32_t *nsplits)
+{
+    if (!pl || !nsplits || r < 0 || r >= pl->problem.batch) return DA_ERR_INVALID_ARG;
+    *nsplits = pl->sched.nsplits[r];
+    return DA_OK;
+}
+
+da_status da_plan_split(const da_plan *pl, int32_t r, int32_t j, int32_t *first_block, int32_t *num_blocks)
+{
+    if (!pl || !first_block || !num_blocks || r < 0 || r >= pl->problem.batch) return DA_ERR_INVALID_ARG;
+    const int64_t ns = pl->sched.nsplits[r];
+    if (j < 0 || j >= ns) return DA_ERR_INVALID_ARG;
+    // same cut as the kernels: split j = [j*nb/ns, (j+1)*nb/ns)
+    const int64_t nb = pl->sched.nblocks[r];
+    const int64_t b0 = (int64_t)j * nb / ns, b1 = ((int64_t)j + 1) * nb / ns;
+    *first_block = (int32_t)b0;
+    *num_blocks = (int32_t)(b1 - b0);
+    return DA_OK;
+}
+
+da_status da_workspace_bytes(const da_plan *pl, size_t *bytes)
+{
+    if (!pl || !bytes) return DA_ERR_INVALID_ARG;
+    const size_t n = (size_t)pl->sched.num_partials;
+    *bytes = align_up(n * da::kHeadDim * sizeof(float), 256) + 2 * align_up(n * sizeof(float), 256);
+    return DA_OK;
+}
+
+da_status da_plan_error(da_plan *pl, void *stream, int32_t *flags)
+{
+    if (!pl || !flags) return DA_ERR_INVALID_ARG;
+    const TableLayout lay(pl->problem.batch);
+    hipStream_t s = (hipStream_t)stream;
+    int32_t v = 0;
+    if (hipMemcpyAsync(&v, pl->dev + lay.err, sizeof v, hipMemcpyDeviceToHost, s) != hipSuccess) return DA_ERR_HIP;
+    if (hipMemsetAsync(pl->dev + lay.err, 0, sizeof v, s) != hipSuccess) return DA_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return DA_ERR_HIP;
+    *flags = v;
+    return DA_OK;
+}
+
+da_status da_partial(const da_plan *pl, const void *q, const void *k_pool, const void *v_pool,
+                     const int32_t *block_table, const int32_t *seq_lens, float *part_o, float *part_m,
+                     float *part_e, void *stream)
+{
+    if (!pl || !q || !k_pool || !v_pool || !block_table || !seq_lens || !part_o || !part_m || !part_e)
+        return DA_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(part_o)) return DA_ERR_INVALID_ARG;
+    da::MicroParams mp = {};
+    fill_micro(pl, mp);
+    mp.q = q;
+    mp.k_pool = k_pool;
+    mp.v_pool = v_pool;
+    mp.block_table = block_table;
+    mp.seq_lens = seq_lens;
+    mp.part_o = part_o;
+    mp.part_m = part_m;
+    mp.part_e = part_e;
+    mp.direct_out = 0;
+    return launch_micro(pl, mp, (hipStream_t)stream);
+}
+
+da_status da_combine(const da_plan *pl, const float *part_o, const float *part_m, const float *part_e, float *out,
+                     float *lse, void *stream)
+{
+    if (!pl || !part_o || !part_m || !part_e || !out) return DA_ERR_INVALID_ARG;
+    if (!aligned16(part_o) || !aligned16(out)) return DA_ERR_INVALID_ARG;
+    da::CombineParams cp = {};
+    fill_combine(pl, cp);
+    cp.part_o = part_o;
+    cp.part_m = part_m;
+    cp.part_e = part_e;
+    cp.out = out;
+    cp.lse = lse;
+    cp.skip_single = 0;
+    return da::launch_combine(cp, (hipStream_t)stream) == hipSuccess ? DA_OK : DA_ERR_HIP;
+}
+
+da_status da_attention(const da_plan *pl, const void *q, const void *k_pool, const void *v_pool,
+                       const int32_t *block_table, const int32_t *seq_lens, float *out, float *lse, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    if (!pl || !q || !k_pool || !v_pool || !block_table || !seq_lens || !out) return DA_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out)) return DA_ERR_INVALID_ARG;
+    size_t need = 0;
+    da_workspace_bytes(pl, &need);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return DA_ERR_WORKSPACE;
+    const size_t n = (size_t)pl->sched.num_partials;
+    char *ws = (char *)workspace;
+    float *part_o = (float *)ws;
+    float *part_m = (float *)(ws + align_up(n * da::kHeadDim * sizeof(float), 256));
+    float *part_e = (float *)((char *)part_m + align_up(n * sizeof(float), 256));
+
+    da::MicroParams mp = {};
+    fill_micro(pl, mp);
+    mp.q = q;
+    mp.k_pool = k_pool;
+    mp.v_pool = v_pool;
+    mp.block_table = block_table;
+    mp.seq_lens = seq_lens;
+    mp.part_o = part_o;
+    mp.part_m = part_m;
+    mp.part_e = part_e;
+    mp.out = out;
+    mp.lse = lse;
+    mp.direct_out = 1;
+    da_status st = launch_micro(pl, mp, (hipStream_t)stream);
+    if (st != DA_OK) return st;
+    if (pl->sched.max_nsplits <= 1) return DA_OK;  // every request was normalised in the MicroAttention kernel
+
+    da::CombineParams cp = {};
+    fill_combine(pl, cp);
+    cp.part_o = part_o;
+    cp.part_m = part_m;
+    cp.part_e = part_e;
+    cp.out = out;
+    cp.lse = lse;
+    cp.skip_single = 1;
+    return da::launch_combine(cp, (hipStream_t)stream) == hipSuccess ? DA_OK : DA_ERR_HIP;
+}
+
+}  // extern "C"

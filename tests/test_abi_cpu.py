@@ -1,0 +1,125 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares, validates its
+arguments before touching the GPU, and its host scheduler cuts the work sensibly.  No kernel runs here."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2401_02669_amd import distattn as da
+from paper_2401_02669_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def problem(B=2, Hq=8, Hkv=2, d=128, T=256, max_blocks=64, num_phys=256, kv=da.DA_BF16, q=da.DA_BF16,
+            scale=0.088, token_stride=None):
+    p = da.DaProblem()
+    p.batch, p.num_q_heads, p.num_kv_heads, p.head_dim = B, Hq, Hkv, d
+    p.block_tokens, p.max_blocks_per_seq, p.num_phys_blocks = T, max_blocks, num_phys
+    p.kv_dtype, p.q_dtype, p.scale = kv, q, scale
+    ts = d if token_stride is None else token_stride
+    p.kv_token_stride, p.kv_head_stride, p.kv_block_stride = ts, ts * T, ts * T * Hkv
+    return p
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "distattn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(da_[a-z_]+)\s*\(", header))
+    assert declared == set(da.EXPORTS), declared ^ set(da.EXPORTS)
+    L = da.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert da.status_string(da.DA_OK) == "ok"
+    assert "unsupported" in da.status_string(da.DA_ERR_UNSUPPORTED)
+
+
+@pytest.mark.parametrize("kwargs,status", [
+    (dict(B=0), da.DA_ERR_INVALID_ARG),
+    (dict(Hq=6, Hkv=4), da.DA_ERR_INVALID_ARG),
+    (dict(d=64), da.DA_ERR_UNSUPPORTED),
+    (dict(T=100), da.DA_ERR_UNSUPPORTED),
+    (dict(T=0), da.DA_ERR_INVALID_ARG),
+    (dict(kv=7), da.DA_ERR_UNSUPPORTED),
+    (dict(scale=float("nan")), da.DA_ERR_INVALID_ARG),
+    (dict(token_stride=100), da.DA_ERR_INVALID_ARG),
+    (dict(token_stride=132), da.DA_ERR_INVALID_ARG),   # bf16 rows would start off a 16-byte boundary
+    (dict(Hq=130, Hkv=1), da.DA_ERR_UNSUPPORTED),
+])
+def test_validation_status_codes(kwargs, status):
+    p = problem(**kwargs)
+    with pytest.raises(da.DistAttnError) as e:
+        da.plan_schedule(p, [10] * max(p.batch, 1))
+    assert e.value.status == status
+
+
+def test_schedule_rejects_bad_lengths_and_null_pointers():
+    p = problem()
+    with pytest.raises(da.DistAttnError) as e:
+        da.plan_schedule(p, [-1, 5])
+    assert e.value.status == da.DA_ERR_INVALID_ARG
+    with pytest.raises(da.DistAttnError) as e:
+        da.plan_schedule(p, [64 * 256 + 1, 5])  # longer than the block table row can address
+    assert e.value.status == da.DA_ERR_INVALID_ARG
+    L = da.lib()
+    assert L.da_plan_schedule(None, None, None, None, None, None, None, None) == da.DA_ERR_INVALID_ARG
+    assert L.da_plan_create(None, None, None, None, None) == da.DA_ERR_INVALID_ARG
+    assert L.da_partial(*([None] * 10)) == da.DA_ERR_INVALID_ARG
+    assert L.da_combine(*([None] * 7)) == da.DA_ERR_INVALID_ARG
+    assert L.da_attention(*([None] * 9), 0, None) == da.DA_ERR_INVALID_ARG
+    assert L.da_workspace_bytes(None, None) == da.DA_ERR_INVALID_ARG
+    assert L.da_plan_destroy(None) == da.DA_OK
+
+
+def _items_per_request(p, ns, kernel):
+    G = p.num_q_heads // p.num_kv_heads
+    tile = 16 if kernel == da.DA_KERNEL_MFMA else min(8, 1 << max(0, math.ceil(math.log2(G))))
+    return ns * p.num_kv_heads * ((G + tile - 1) // tile)
+
+
+@pytest.mark.parametrize("name", list(synth.WORKLOADS))
+def test_schedule_properties_on_the_five_workloads(name):
+    r = synth.recipe(name)
+    rng = np.random.RandomState(synth.BASE_SEED + r["index"])
+    lens = synth._lengths(r, rng)
+    T = r["T"]
+    nb = (lens + T - 1) // T
+    p = problem(B=r["B"], Hq=r["Hq"], Hkv=r["Hkv"], T=T, max_blocks=int(nb.max()), num_phys=int(nb.sum()),
+                kv=da.DA_F32 if r["dtype"] == "f32" else da.DA_BF16,
+                q=da.DA_F32 if r["dtype"] == "f32" else da.DA_BF16)
+    s = da.plan_schedule(p, lens, num_cus=256)
+    ns = np.array(s["nsplits"])
+    assert np.all(ns >= 1) and np.all(ns <= np.maximum(nb, 1))
+    assert sorted(s["order"]) == list(range(r["B"]))
+    order_nb = nb[np.array(s["order"])]
+    assert np.all(order_nb[:-1] >= order_nb[1:])  # longest first
+    assert s["num_partials"] == int(ns.sum()) * r["Hq"]
+    assert s["num_items"] == sum(_items_per_request(p, int(n), s["kernel"]) for n in ns)
+    # every block belongs to exactly one split, and splits of one request differ by at most one block
+    for i in range(r["B"]):
+        cuts = [(j * int(nb[i])) // int(ns[i]) for j in range(int(ns[i]) + 1)]
+        sizes = np.diff(cuts)
+        assert cuts[0] == 0 and cuts[-1] == nb[i] and np.all(sizes >= 0)
+        assert sizes.max() - sizes.min() <= 1
+    if name != "c1_tiny":
+        # enough items to keep 256 CUs x 2 resident workgroups busy many times over, and partial rows
+        # (written once, read once) stay a small fraction of the KV bytes
+        assert s["num_items"] >= 256 * 2 * 8
+        esize = 2
+        partial_bytes = 2.0 * s["num_partials"] * (128 + 2) * 4
+        kv_bytes = float(lens.sum()) * r["Hkv"] * 2 * 128 * esize
+        assert partial_bytes / kv_bytes < 0.03
+
+
+def test_explicit_blocks_per_split_is_honoured():
+    p = problem(B=3, max_blocks=100)
+    lens = [100 * 256, 1, 0]
+    s = da.plan_schedule(p, lens, blocks_per_split=1)
+    assert s["nsplits"] == [100, 1, 1]
+    s = da.plan_schedule(p, lens, blocks_per_split=7)
+    assert s["nsplits"] == [15, 1, 1]
+    s = da.plan_schedule(p, lens, blocks_per_split=1000)
+    assert s["nsplits"] == [1, 1, 1]

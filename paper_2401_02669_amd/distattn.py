@@ -194,9 +194,9 @@ class Plan:
 
     # ---- launches -------------------------------------------------------------------------
     def partial(self, q, k_pool, v_pool, block_table, seq_lens, part_o=None, part_m=None, part_e=None, stream=None):
-        n = self.num_partials
-        dev = q.device
         if part_o is None:
+            n = self.num_partials
+            dev = k_pool.device
             part_o = torch.empty((n, self.problem.head_dim), dtype=torch.float32, device=dev)
             part_m = torch.empty((n,), dtype=torch.float32, device=dev)
             part_e = torch.empty((n,), dtype=torch.float32, device=dev)

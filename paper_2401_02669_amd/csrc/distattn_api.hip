@@ -10,6 +10,7 @@
 
 namespace da {
 hipError_t launch_micro_attention_valu(const MicroParams &p, bool kv_bf16, int64_t num_items, hipStream_t stream);
+hipError_t launch_micro_attention_mfma(const MicroParams &p, int64_t num_items, hipStream_t stream);
 hipError_t launch_combine(const CombineParams &p, hipStream_t stream);
 }  // namespace da
 
@@ -102,6 +103,8 @@ da_status launch_micro(const da_plan *pl, const da::MicroParams &mp, hipStream_t
     hipError_t e = hipErrorInvalidValue;
     if (pl->sched.kernel == DA_KERNEL_VALU)
         e = da::launch_micro_attention_valu(mp, pl->problem.kv_dtype == DA_BF16, pl->sched.num_items, stream);
+    else if (pl->sched.kernel == DA_KERNEL_MFMA)
+        e = da::launch_micro_attention_mfma(mp, pl->sched.num_items, stream);
     return e == hipSuccess ? DA_OK : DA_ERR_HIP;
 }
 

@@ -1,0 +1,313 @@
+// MicroAttention on the matrix cores, for grouped-query attention with bf16 q / K / V
+// (Section 4, m_j / e_j equation and Eq. 2; Section 3: the q-heads of a GQA group share one K/V read).
+//
+// One workgroup (8 wavefronts) owns one work item: a run of KV blocks of one (request, kv-head) and
+// a tile of up to 16 q-heads of its group.  Each wavefront walks 32-token chunks on its own:
+//
+//   S  = K  . Q^T   v_mfma_f32_16x16x32_bf16, A = 16 token rows of K (16 B of a row per lane, loaded
+//                   straight from HBM in operand layout), B = Q^T (head = lane % 16).  bf16 x bf16
+//                   products are exact and summed in fp32.
+//   P  = exp2(S * scale*log2e - m), running m / e per head (head = lane % 16 in every step).
+//   O^T += V^T . P^T  A = V^T: a lane loads the same 16-byte column slice of 8 token rows (so a load
+//                   instruction fetches whole 256-byte rows) and interleaves them in registers with
+//                   v_perm_b32; B = P^T, which is exactly how the lane already holds P.  P is split
+//                   into bf16 high + low parts (two MFMAs) so that it keeps 16 bits of mantissa.
+//
+// Heads beyond the group (lanes with lane % 16 >= G) carry q = 0 and are never written.
+#include <hip/hip_runtime.h>
+
+#include "kernel_params.h"
+
+namespace da {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kNegInf = -__builtin_inff();
+constexpr float kLn2 = 0.69314718055994530942f;
+constexpr int kHeadTile = 16;  // q-heads per work item (MFMA N dimension)
+constexpr int kChunk = 32;     // tokens per wavefront step (MFMA K dimension of the PV product)
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+// Two floats -> packed bf16 (round to nearest even), first value in the low half.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+__device__ __forceinline__ f32x4 mfma_bf16(const uint4 &a, const uint4 &b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+__global__ __launch_bounds__(kThreads) void micro_attention_mfma_kernel(const MicroParams p)
+{
+    // cross-wavefront merge buffers (live heads only are touched)
+    __shared__ float lds_m[kWavesPerGroup][kHeadTile];
+    __shared__ float lds_e[kWavesPerGroup][kHeadTile];
+    __shared__ float lds_o[kWavesPerGroup][kHeadTile][kHeadDim];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int lg = lane >> 4;   // lane group: k-slice of the MFMA operands
+    const int ln = lane & 15;   // token row (K operand) / head (Q, P operands, results)
+
+    // ---- which work item -------------------------------------------------------------------
+    const int item = blockIdx.x;
+    int lo = 0, hi = p.B;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (p.item_prefix[mid] <= item) lo = mid; else hi = mid;
+    }
+    const int r = p.order[lo];
+    const int local = item - p.item_prefix[lo];
+    const int ns = p.nsplits[r];
+    const int per_split = p.Hkv * p.head_tiles;
+    const int j = local / per_split;
+    const int rem = local - j * per_split;
+    const int kvh = rem / p.head_tiles;
+    const int ht = rem - kvh * p.head_tiles;
+
+    const int T = p.T;
+    int L = p.seq_lens[r];
+    L = L < 0 ? 0 : L;
+    const int64_t cap = (int64_t)p.max_blocks * T;
+    if ((int64_t)L > cap) L = (int)cap;
+    const int nb = (L + T - 1) / T;
+    const int b0 = (int)(((int64_t)j * nb) / ns);
+    const int b1 = (int)(((int64_t)(j + 1) * nb) / ns);
+
+    // ---- Q^T operand: head = ln, k-slice lg of each of the 4 k-steps -------------------------------
+    const int hl = ht * kHeadTile + ln;  // head inside the group
+    const bool live = hl < p.G;
+    uint4 qreg[4];
+    {
+        const uint16_t *q = (const uint16_t *)p.q + ((int64_t)r * p.Hq + (int64_t)kvh * p.G + (live ? hl : 0)) * kHeadDim;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            qreg[ks] = *(const uint4 *)(q + ks * 32 + lg * 8);
+            if (!live) qreg[ks] = make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+    const float c2 = p.scale_log2e;
+
+    float m = kNegInf;   // running maximum of head ln's scores, base-2 units (all lane groups agree)
+    float e = 0.0f;      // this lane's share of the exp-sum (its 8 tokens per chunk)
+    f32x4 acc[8];        // O^T: acc[n][i] = O[head ln][column 32*lg + 8*i + n]
+#pragma unroll
+    for (int n = 0; n < 8; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- chunk walk -----------------------------------------------------------------------------
+    const int cpb = (T + kChunk - 1) / kChunk;
+    const int nchunks = (b1 - b0) * cpb;
+    const char *kbase = (const char *)p.k_pool;
+    const char *vbase = (const char *)p.v_pool;
+    const int64_t row_bytes = p.stride_token * 2;
+    // K: lane reads token (16*mb + ln), bytes [64*ks + 16*lg, +16) of the row
+    const int64_t k_lane_off = (int64_t)ln * row_bytes + lg * 16;
+    // V: lane reads token (16*(jj/4) + 4*lg + jj%4), bytes [16*ln, +16) of the row
+    const int64_t v_lane_off = (int64_t)(4 * lg) * row_bytes + ln * 16;
+
+    struct Chunk {
+        int n, blk, cib;
+        int lim;       // valid tokens from the chunk's first row on (<= 0: none)
+        int64_t off;   // byte offset of the chunk's first row in a pool
+    };
+    auto locate = [&](Chunk &c) {
+        c.lim = 0;
+        c.off = 0;
+        if (c.n >= nchunks) return;
+        const int pb = p.block_table[(int64_t)r * p.max_blocks + c.blk];
+        const int first = c.cib * kChunk;
+        int valid = L - c.blk * T;
+        valid = (valid > T ? T : valid) - first;
+        if ((unsigned)pb >= (unsigned)p.num_phys) {
+            if (lane == 0) atomicOr(p.err_flag, 1);
+            valid = 0;
+        }
+        c.lim = valid;
+        c.off = ((int64_t)pb * p.stride_block + (int64_t)kvh * p.stride_head + (int64_t)first * p.stride_token) * 2;
+    };
+    auto advance = [&](Chunk c) {
+        c.n += kWavesPerGroup;
+        c.cib += kWavesPerGroup;
+        while (c.cib >= cpb) {
+            c.cib -= cpb;
+            c.blk += 1;
+        }
+        locate(c);
+        return c;
+    };
+    auto load_k = [&](const Chunk &c, uint4 (&dst)[8]) {
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            const bool ok = mb * 16 + ln < c.lim;
+            const char *row = kbase + c.off + k_lane_off + (int64_t)(mb * 16) * row_bytes;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                dst[mb * 4 + ks] = make_uint4(0u, 0u, 0u, 0u);
+                if (ok) dst[mb * 4 + ks] = *(const uint4 *)(row + ks * 64);
+            }
+        }
+    };
+    auto load_v = [&](const Chunk &c, uint4 (&dst)[8]) {
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            const int tok = 16 * (jj >> 2) + (jj & 3);  // + 4*lg, folded into v_lane_off
+            dst[jj] = make_uint4(0u, 0u, 0u, 0u);
+            if (tok + 4 * lg < c.lim) dst[jj] = *(const uint4 *)(vbase + c.off + v_lane_off + (int64_t)tok * row_bytes);
+        }
+    };
+
+    Chunk cur;
+    cur.n = wave;
+    cur.blk = b0 + wave / cpb;
+    cur.cib = wave % cpb;
+    locate(cur);
+
+    uint4 kr[8], vr[8];
+    if (cur.n < nchunks) load_k(cur, kr);
+
+    while (cur.n < nchunks) {
+        load_v(cur, vr);
+        const Chunk nxt = advance(cur);
+
+        // S[token 16*mb + 4*lg + i][head ln] for mb = 0, 1
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            s0 = mfma_bf16(kr[ks], qreg[ks], s0);
+            s1 = mfma_bf16(kr[4 + ks], qreg[ks], s1);
+        }
+        if (nxt.n < nchunks) load_k(nxt, kr);
+
+        // scores in base-2 units (scale * log2(e) applied), rows past the valid tokens masked out
+        float s[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            s[i] = (4 * lg + i < cur.lim) ? s0[i] * c2 : kNegInf;
+            s[4 + i] = (16 + 4 * lg + i < cur.lim) ? s1[i] * c2 : kNegInf;
+        }
+        float cm = s[0];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) cm = fmaxf(cm, s[i]);
+        cm = fmaxf(cm, __shfl_xor(cm, 16));
+        cm = fmaxf(cm, __shfl_xor(cm, 32));
+        const float mn = fmaxf(m, cm);
+        const float mu = (mn == kNegInf) ? 0.0f : mn;
+        const float alpha = fast_exp2(m - mu);
+        m = mn;
+        float sum = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            s[i] = fast_exp2(s[i] - mu);
+            sum += s[i];
+        }
+        e = fmaf(e, alpha, sum);
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+            for (int n = 0; n < 8; ++n) acc[n] *= alpha;
+        }
+
+        // P^T operand: 8 tokens of this lane group, head ln; high and low bf16 parts
+        uint4 ph, pl;
+        {
+            uint32_t h[4], l[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                h[t] = pack_bf16(s[2 * t], s[2 * t + 1]);
+                const float r0 = s[2 * t] - as_f(h[t] << 16);
+                const float r1 = s[2 * t + 1] - as_f(h[t] & 0xFFFF0000u);
+                l[t] = pack_bf16(r0, r1);
+            }
+            ph = make_uint4(h[0], h[1], h[2], h[3]);
+            pl = make_uint4(l[0], l[1], l[2], l[3]);
+        }
+
+        // O^T += V^T . P^T, 8 MFMA column groups; column group n takes columns 8*m + n, m = MFMA row
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const uint32_t d0 = (&vr[0].x)[w], d1 = (&vr[1].x)[w], d2 = (&vr[2].x)[w], d3 = (&vr[3].x)[w];
+            const uint32_t d4 = (&vr[4].x)[w], d5 = (&vr[5].x)[w], d6 = (&vr[6].x)[w], d7 = (&vr[7].x)[w];
+            // even column 2w: low halves; odd column 2w+1: high halves; (token 2t, token 2t+1) per register
+            const uint4 ve = make_uint4(__builtin_amdgcn_perm(d1, d0, 0x05040100u), __builtin_amdgcn_perm(d3, d2, 0x05040100u),
+                                        __builtin_amdgcn_perm(d5, d4, 0x05040100u), __builtin_amdgcn_perm(d7, d6, 0x05040100u));
+            const uint4 vo = make_uint4(__builtin_amdgcn_perm(d1, d0, 0x07060302u), __builtin_amdgcn_perm(d3, d2, 0x07060302u),
+                                        __builtin_amdgcn_perm(d5, d4, 0x07060302u), __builtin_amdgcn_perm(d7, d6, 0x07060302u));
+            acc[2 * w] = mfma_bf16(ve, ph, acc[2 * w]);
+            acc[2 * w] = mfma_bf16(ve, pl, acc[2 * w]);
+            acc[2 * w + 1] = mfma_bf16(vo, ph, acc[2 * w + 1]);
+            acc[2 * w + 1] = mfma_bf16(vo, pl, acc[2 * w + 1]);
+        }
+        cur = nxt;
+    }
+
+    // ---- wavefront result: exp-sum over the lane groups; m is already common ---------------------
+    e += __shfl_xor(e, 16);
+    e += __shfl_xor(e, 32);
+    if (live) {
+        if (lg == 0) {
+            lds_m[wave][ln] = m;
+            lds_e[wave][ln] = e;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float *dst = &lds_o[wave][ln][32 * lg + 8 * i];
+            *(float4 *)dst = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
+            *(float4 *)(dst + 4) = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
+        }
+    }
+    __syncthreads();
+
+    // ---- merge the wavefronts and write the item's result -----------------------------------------
+    const bool direct = p.direct_out && ns == 1;
+    int heads = p.G - ht * kHeadTile;
+    heads = heads > kHeadTile ? kHeadTile : heads;
+    for (int idx = tid; idx < heads * kHeadDim; idx += kThreads) {
+        const int g = idx / kHeadDim, col = idx % kHeadDim;
+        float M = lds_m[0][g];
+#pragma unroll
+        for (int w = 1; w < kWavesPerGroup; ++w) M = fmaxf(M, lds_m[w][g]);
+        const float mu = (M == kNegInf) ? 0.0f : M;
+        float o = 0.0f, E = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWavesPerGroup; ++w) {
+            const float wgt = fast_exp2(lds_m[w][g] - mu);
+            o = fmaf(lds_o[w][g][col], wgt, o);
+            E = fmaf(lds_e[w][g], wgt, E);
+        }
+        const int h = kvh * p.G + ht * kHeadTile + g;
+        const float m_nat = M * kLn2;  // base-2 -> natural-log score units (-inf stays -inf)
+        if (direct) {
+            const int64_t orow = (int64_t)r * p.Hq + h;
+            p.out[orow * kHeadDim + col] = (E > 0.0f) ? o / E : 0.0f;
+            if (col == 0 && p.lse) p.lse[orow] = (E > 0.0f) ? m_nat + __logf(E) : kNegInf;
+        } else {
+            const int64_t prow = p.row_base[r] + (int64_t)h * ns + j;
+            p.part_o[prow * kHeadDim + col] = o;
+            if (col == 0) {
+                p.part_m[prow] = m_nat;
+                p.part_e[prow] = E;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_micro_attention_mfma(const MicroParams &p, int64_t num_items, hipStream_t stream)
+{
+    if (num_items <= 0) return hipSuccess;
+    if (p.head_tile != kHeadTile || !p.q_bf16) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(micro_attention_mfma_kernel, dim3((unsigned)num_items), dim3(kThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace da

@@ -17,7 +17,6 @@ namespace {
 constexpr int kResidentGroupsPerCu = 2;  // 8-wave MicroAttention workgroups resident per compute unit
 constexpr int kItemsPerSlot = 32;        // wanted items per resident workgroup: keeps the tail short
 constexpr double kPartialBudget = 0.015; // partial write + read traffic allowed, relative to KV bytes
-constexpr bool kHaveMfmaKernel = false;  // the matrix-core MicroAttention kernel is not built yet
 }
 
 da_status validate_problem(const da_problem &p)
@@ -54,7 +53,7 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
 
     // kernel family and head tile
     int kernel = tuning.kernel;
-    const bool mfma_ok = kHaveMfmaKernel && p.kv_dtype == DA_BF16 && p.q_dtype == DA_BF16;
+    const bool mfma_ok = p.kv_dtype == DA_BF16 && p.q_dtype == DA_BF16;
     if (kernel == DA_KERNEL_AUTO) kernel = (G > 1 && mfma_ok) ? DA_KERNEL_MFMA : DA_KERNEL_VALU;
     if (kernel == DA_KERNEL_MFMA && !mfma_ok) return DA_ERR_UNSUPPORTED;
     s.kernel = kernel;

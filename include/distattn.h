@@ -179,6 +179,17 @@ da_status da_attention(const da_plan *plan, const void *q, const void *k_pool, c
                        const int32_t *block_table, const int32_t *seq_lens, float *out, float *lse,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Measurement aid, not part of the attention path: streams `bytes` of device memory once with
+ * 16-byte-per-lane loads and discards the data, so that a caller can time the HBM read rate a pure
+ * streaming kernel sustains on this GPU (the ceiling the MicroAttention kernels are reported against).
+ * `workgroups` workgroups of 512 threads walk `segment_bytes` segments round-robin; `variant` picks
+ * the loads in flight per wavefront (0: 4, 1: 8, 2: 16, 3: 8 non-temporal, 4: 16 non-temporal).
+ * `sink` is 4 bytes of device memory.
+ */
+da_status da_probe_read(const void *src, size_t bytes, size_t segment_bytes, int32_t workgroups, int32_t variant,
+                        void *sink, void *stream);
+
 const char *da_status_string(da_status status);
 
 #ifdef __cplusplus

@@ -13,7 +13,13 @@
 namespace da {
 namespace {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+// 16-byte streaming load: K and V are read exactly once, so the non-temporal hint keeps them from
+// displacing anything in the caches (measurably faster than a plain load on this GPU).
+__device__ __forceinline__ u32x4 load16_stream(const char *p) { return __builtin_nontemporal_load((const u32x4 *)p); }
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float x)
@@ -47,7 +53,7 @@ struct Slice;  // a lane's 16 bytes of one token row
 template <>
 struct Slice<true> {
     static constexpr int N = 8;
-    static __device__ __forceinline__ void unpack(const uint4 &r, float (&f)[8])
+    static __device__ __forceinline__ void unpack(const u32x4 &r, float (&f)[8])
     {
         f[0] = as_f(r.x << 16); f[1] = as_f(r.x & 0xFFFF0000u);
         f[2] = as_f(r.y << 16); f[3] = as_f(r.y & 0xFFFF0000u);
@@ -58,7 +64,7 @@ struct Slice<true> {
 template <>
 struct Slice<false> {
     static constexpr int N = 4;
-    static __device__ __forceinline__ void unpack(const uint4 &r, float (&f)[4])
+    static __device__ __forceinline__ void unpack(const u32x4 &r, float (&f)[4])
     {
         f[0] = as_f(r.x); f[1] = as_f(r.y); f[2] = as_f(r.z); f[3] = as_f(r.w);
     }
@@ -178,11 +184,11 @@ __global__ __launch_bounds__(kThreads) void micro_attention_valu_kernel(const Mi
         locate(c);
         return c;
     };
-    auto load_rows = [&](const char *base, const Chunk &c, uint4 (&dst)[NL]) {
+    auto load_rows = [&](const char *base, const Chunk &c, u32x4 (&dst)[NL]) {
 #pragma unroll
         for (int jj = 0; jj < NL; ++jj) {
-            dst[jj] = make_uint4(0u, 0u, 0u, 0u);
-            if (jj * RPL + row < c.lim) dst[jj] = *(const uint4 *)(base + c.off + jj * load_step);
+            dst[jj] = u32x4{0u, 0u, 0u, 0u};
+            if (jj * RPL + row < c.lim) dst[jj] = load16_stream(base + c.off + jj * load_step);
         }
     };
 
@@ -192,7 +198,7 @@ __global__ __launch_bounds__(kThreads) void micro_attention_valu_kernel(const Mi
     cur.cib = wave % cpb;
     locate(cur);
 
-    uint4 kr[NL], vr[NL];
+    u32x4 kr[NL], vr[NL];
     if (cur.n < nchunks) load_rows(kbase, cur, kr);
 
     while (cur.n < nchunks) {

@@ -1,0 +1,55 @@
+// Read-ceiling probe: streams a device buffer once with the same 16-byte-per-lane loads the
+// MicroAttention kernels use and only adds the words up.  It measures the HBM read rate this GPU
+// sustains for a pure streaming kernel, the practical ceiling the attention kernels are compared to.
+#include <hip/hip_runtime.h>
+
+#include "../../include/distattn.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Each workgroup owns consecutive `seg_bytes` segments (round-robin over the grid); a wavefront reads
+// 1 KiB per load instruction, UNROLL loads in flight.
+template <int UNROLL, bool NT>
+__global__ __launch_bounds__(512) void read_probe_kernel(const u32x4 *src, size_t n16, size_t seg16, uint32_t *sink)
+{
+    const size_t nseg = (n16 + seg16 - 1) / seg16;
+    uint32_t acc = 0;
+    for (size_t seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
+        const size_t lo = seg * seg16;
+        const size_t hi = lo + seg16 < n16 ? lo + seg16 : n16;
+        for (size_t i = lo + threadIdx.x; i < hi; i += (size_t)512 * UNROLL) {
+            u32x4 v[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const size_t k = i + (size_t)u * 512;
+                v[u] = u32x4{0u, 0u, 0u, 0u};
+                if (k < hi) v[u] = NT ? __builtin_nontemporal_load(src + k) : src[k];
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+        }
+    }
+    if (acc == 0x9E3779B9u) sink[0] = acc;  // keeps the loads alive; practically never taken
+}
+
+}  // namespace
+
+extern "C" da_status da_probe_read(const void *src, size_t bytes, size_t segment_bytes, int32_t workgroups,
+                                   int32_t variant, void *sink, void *stream)
+{
+    if (!src || !sink || bytes < 16 || segment_bytes < 16 || workgroups < 1 || ((uintptr_t)src & 15)) return DA_ERR_INVALID_ARG;
+    const size_t n16 = bytes / 16, seg16 = segment_bytes / 16;
+    hipStream_t s = (hipStream_t)stream;
+    dim3 grid((unsigned)workgroups), block(512);
+    switch (variant) {
+    case 0: hipLaunchKernelGGL((read_probe_kernel<4, false>), grid, block, 0, s, (const u32x4 *)src, n16, seg16, (uint32_t *)sink); break;
+    case 1: hipLaunchKernelGGL((read_probe_kernel<8, false>), grid, block, 0, s, (const u32x4 *)src, n16, seg16, (uint32_t *)sink); break;
+    case 2: hipLaunchKernelGGL((read_probe_kernel<16, false>), grid, block, 0, s, (const u32x4 *)src, n16, seg16, (uint32_t *)sink); break;
+    case 3: hipLaunchKernelGGL((read_probe_kernel<8, true>), grid, block, 0, s, (const u32x4 *)src, n16, seg16, (uint32_t *)sink); break;
+    case 4: hipLaunchKernelGGL((read_probe_kernel<16, true>), grid, block, 0, s, (const u32x4 *)src, n16, seg16, (uint32_t *)sink); break;
+    default: return DA_ERR_INVALID_ARG;
+    }
+    return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
+}

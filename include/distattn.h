@@ -92,7 +92,7 @@ typedef struct {
 
 /* Scheduling knobs; a NULL da_tuning* or a zero field means "choose". */
 typedef struct {
-    int32_t blocks_per_split; /* KV blocks per MicroAttention; 1 = one partial per block as in Section 4 */
+    int32_t blocks_per_split; /* KV blocks per MicroAttention; 1 = one partial per block as in Section 4; 0 = balanced */
     int32_t num_cus;          /* compute units to fill; 0 = ask the device (256 on MI355X) */
     int32_t kernel;           /* da_kernel */
 } da_tuning;
@@ -102,9 +102,12 @@ typedef struct da_plan da_plan; /* opaque: split schedule of one batch + its sma
 /*
  * Work scheduling (host).  Section 5.3, Eq. 5 prices attention by total KV
  * length, not batch size; Section 3 allows partitions of any length.  The
- * plan therefore cuts every request's blocks into nsplits[r] near-equal runs
- * ("splits") sized so that the (split, kv-head) work items keep every compute
- * unit busy, from one short request to one 2M-token request.
+ * plan therefore cuts every request's tokens into nsplits[r] near-equal runs
+ * ("splits"), each starting and ending on a 32-token tile of a block and of
+ * about the same size across the whole batch, so that the (split, kv-head)
+ * work items keep every compute unit equally busy, from one short request to
+ * one 2M-token request.  With da_tuning.blocks_per_split > 0 every split is
+ * exactly that many blocks instead.
  *
  * da_plan_schedule: pure host arithmetic, no HIP call.  Writes nsplits[r]
  *   (>= 1; 1 for an empty request) into nsplits_host[batch] and the processing
@@ -132,8 +135,8 @@ da_status da_plan_destroy(da_plan *plan);
 
 /* Rows of part_o / part_m / part_e for this plan. */
 da_status da_plan_num_partials(const da_plan *plan, int64_t *num_partials);
-/* Split j of request r covers logical blocks [*first_block, *first_block + *num_blocks). */
-da_status da_plan_split(const da_plan *plan, int32_t r, int32_t j, int32_t *first_block, int32_t *num_blocks);
+/* Split j of request r covers the logical tokens [*first_token, *end_token) (possibly none). */
+da_status da_plan_split(const da_plan *plan, int32_t r, int32_t j, int64_t *first_token, int64_t *end_token);
 /* nsplits[r]. */
 da_status da_plan_nsplits(const da_plan *plan, int32_t r, int32_t *nsplits);
 /* Bytes of device workspace da_attention needs (the three part_* arrays, 256-byte aligned each). */

@@ -1,6 +1,7 @@
 // C ABI of the DistAttention decode library: argument checks, plan objects, kernel launches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstring>
 #include <new>
 
@@ -9,8 +10,8 @@
 #include "schedule.h"
 
 namespace da {
-hipError_t launch_micro_attention_valu(const MicroParams &p, bool kv_bf16, int64_t num_items, hipStream_t stream);
-hipError_t launch_micro_attention_mfma(const MicroParams &p, int64_t num_items, hipStream_t stream);
+hipError_t launch_micro_attention_valu(const MicroParams &p, bool kv_bf16, int grid, hipStream_t stream);
+hipError_t launch_micro_attention_mfma(const MicroParams &p, int grid, hipStream_t stream);
 hipError_t launch_combine(const CombineParams &p, hipStream_t stream);
 }  // namespace da
 
@@ -42,6 +43,7 @@ struct da_plan {
     int32_t num_cus;
     int device;
     da::Schedule sched;
+    std::vector<int32_t> lens;  // host lengths the schedule was made from
     char *dev = nullptr;       // device tables (+ error flag at layout.err)
     size_t dev_bytes = 0;
     char *stage[kRing] = {};   // pinned host staging
@@ -92,6 +94,8 @@ void fill_micro(const da_plan *pl, da::MicroParams &mp)
     mp.head_tile = pl->sched.head_tile;
     mp.head_tiles = pl->sched.head_tiles;
     mp.q_bf16 = p.q_dtype == DA_BF16;
+    mp.num_items = (int32_t)pl->sched.num_items;
+    mp.fixed_split_tiles = pl->sched.fixed_split_tiles;
     mp.stride_block = p.kv_block_stride;
     mp.stride_head = p.kv_head_stride;
     mp.stride_token = p.kv_token_stride;
@@ -102,9 +106,9 @@ da_status launch_micro(const da_plan *pl, const da::MicroParams &mp, hipStream_t
 {
     hipError_t e = hipErrorInvalidValue;
     if (pl->sched.kernel == DA_KERNEL_VALU)
-        e = da::launch_micro_attention_valu(mp, pl->problem.kv_dtype == DA_BF16, pl->sched.num_items, stream);
+        e = da::launch_micro_attention_valu(mp, pl->problem.kv_dtype == DA_BF16, pl->sched.grid, stream);
     else if (pl->sched.kernel == DA_KERNEL_MFMA)
-        e = da::launch_micro_attention_mfma(mp, pl->sched.num_items, stream);
+        e = da::launch_micro_attention_mfma(mp, pl->sched.grid, stream);
     return e == hipSuccess ? DA_OK : DA_ERR_HIP;
 }
 
@@ -182,6 +186,7 @@ da_status da_plan_create(const da_problem *problem, const int32_t *seq_lens_host
     pl->num_cus = cus;
     pl->device = device;
     st = da::make_schedule(pl->problem, seq_lens_host, t, cus, pl->sched);
+    if (st == DA_OK) pl->lens.assign(seq_lens_host, seq_lens_host + problem->batch);
     if (st != DA_OK) {
         delete pl;
         return st;
@@ -211,6 +216,7 @@ da_status da_plan_update(da_plan *pl, const int32_t *seq_lens_host, void *stream
     da_status st = da::make_schedule(pl->problem, seq_lens_host, pl->tuning, pl->num_cus, s);
     if (st != DA_OK) return st;
     pl->sched = std::move(s);
+    pl->lens.assign(seq_lens_host, seq_lens_host + pl->problem.batch);
     return upload(pl, (hipStream_t)stream);
 }
 
@@ -241,16 +247,18 @@ da_status da_plan_nsplits(const da_plan *pl, int32_t r, int32_t *nsplits)
     return DA_OK;
 }
 
-da_status da_plan_split(const da_plan *pl, int32_t r, int32_t j, int32_t *first_block, int32_t *num_blocks)
+da_status da_plan_split(const da_plan *pl, int32_t r, int32_t j, int64_t *first_token, int64_t *end_token)
 {
-    if (!pl || !first_block || !num_blocks || r < 0 || r >= pl->problem.batch) return DA_ERR_INVALID_ARG;
-    const int64_t ns = pl->sched.nsplits[r];
+    if (!pl || !first_token || !end_token || r < 0 || r >= pl->problem.batch) return DA_ERR_INVALID_ARG;
+    const int32_t ns = pl->sched.nsplits[r];
     if (j < 0 || j >= ns) return DA_ERR_INVALID_ARG;
-    // same cut as the kernels: split j = [j*nb/ns, (j+1)*nb/ns)
-    const int64_t nb = pl->sched.nblocks[r];
-    const int64_t b0 = (int64_t)j * nb / ns, b1 = ((int64_t)j + 1) * nb / ns;
-    *first_block = (int32_t)b0;
-    *num_blocks = (int32_t)(b1 - b0);
+    // same cut as the kernels, in 32-token tiles of a block
+    int64_t t0, t1;
+    da::split_tiles(pl->sched.ntiles[r], ns, pl->sched.fixed_split_tiles, j, &t0, &t1);
+    const int32_t T = pl->problem.block_tokens;
+    const int64_t L = pl->lens[r];
+    *first_token = std::min<int64_t>(L, da::tile_first_token(t0, T));
+    *end_token = std::min<int64_t>(L, da::tile_first_token(t1, T));
     return DA_OK;
 }
 

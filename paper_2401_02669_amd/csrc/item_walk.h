@@ -1,0 +1,168 @@
+// Device-side walk over work items and their KV chunks, shared by the MicroAttention kernels.
+//
+// An item covers the tiles [t0, t1) of one request (tile = 32 tokens inside a block; a block holds
+// ceil(T / 32) tiles).  A kernel reads it in chunks of CH tokens (CH divides 32); wavefront w of W
+// takes chunks w, w + W, ... of the item.  Everything here is uniform across a wavefront.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "kernel_params.h"
+
+namespace da {
+
+// Read of a small read-only table (plan tables, block table, lengths) at a wavefront-uniform index.
+// Going through the constant address space lets the compiler use scalar loads even after the kernel
+// has stored to global memory; nothing in these kernels writes the tables.
+template <typename T>
+__device__ __forceinline__ T table_load(const T *p, int64_t i)
+{
+    typedef const T __attribute__((address_space(4))) * cptr;
+    return ((cptr)(uintptr_t)p)[i];
+}
+
+struct ItemInfo {
+    int valid;       // 0: past the end of the item list
+    int r, j, kvh, ht, ns;
+    int L;           // tokens of the request (device value, clamped to what the table can address)
+    int c0, c1;      // chunk range of the item, in block-major chunk numbering
+    int64_t row_base;
+};
+
+struct Chunk {
+    int valid;   // 0: past the end of the item
+    int c;       // chunk number
+    int blk;     // logical block
+    int cib;     // chunk inside the block
+    int lim;     // valid tokens from the chunk's first row on (<= 0: none)
+    int64_t off; // element offset of the chunk's first row (this item's kv-head) inside a pool;
+                 // 0 (always readable) when the chunk holds no valid token
+};
+
+// What a wavefront fetches for a chunk.  The kernels issue the same number of load instructions in
+// every step, whatever the chunk (so that the compiler can count outstanding loads exactly and
+// overlap them with arithmetic): rows past the valid ones re-read the last valid row, and a chunk
+// with nothing valid re-reads row 0 of the pool; such rows are masked out of the softmax.
+struct Fetch {
+    int64_t off;  // element offset of the first row
+    int last;     // index of the last row that may be read (>= 0)
+};
+__device__ __forceinline__ Fetch fetch_of(const Chunk &c)
+{
+    Fetch f;
+    const bool any = c.valid && c.lim > 0;
+    f.off = any ? c.off : 0;
+    f.last = any ? c.lim - 1 : 0;
+    return f;
+}
+
+// Item number handled by workgroup `b` in round `k` of a persistent grid of `g` workgroups: rounds
+// alternate direction so that no workgroup always gets the largest item of a size-sorted round.
+__device__ __forceinline__ int item_of(int b, int k, int g) { return k * g + ((k & 1) ? g - 1 - b : b); }
+
+template <int CH>
+__device__ __forceinline__ ItemInfo decode_item(const MicroParams &p, int item)
+{
+    constexpr int SUB = kTile / CH;  // chunks per tile
+    ItemInfo it;
+    it.valid = item < p.num_items;
+    it.r = it.j = it.kvh = it.ht = 0;
+    it.ns = 1;
+    it.L = 0;
+    it.c0 = it.c1 = 0;
+    it.row_base = 0;
+    if (!it.valid) return it;
+    int lo = 0, hi = p.B;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (table_load(p.item_prefix, mid) <= item) lo = mid; else hi = mid;
+    }
+    it.r = table_load(p.order, lo);
+    const int local = item - table_load(p.item_prefix, lo);
+    it.ns = table_load(p.nsplits, it.r);
+    it.row_base = table_load(p.row_base, it.r);
+    const int per_split = p.Hkv * p.head_tiles;
+    it.j = local / per_split;
+    const int rem = local - it.j * per_split;
+    it.kvh = rem / p.head_tiles;
+    it.ht = rem - it.kvh * p.head_tiles;
+
+    const int T = p.T;
+    int L = table_load(p.seq_lens, it.r);
+    L = L < 0 ? 0 : L;
+    const int64_t cap = (int64_t)p.max_blocks * T;
+    if ((int64_t)L > cap) L = (int)cap;
+    it.L = L;
+    const int tpb = (T + kTile - 1) / kTile;
+    int nt = 0;
+    if (L > 0) {
+        const int nb = (L + T - 1) / T;
+        const int tail = L - (nb - 1) * T;
+        nt = (nb - 1) * tpb + (tail + kTile - 1) / kTile;
+    }
+    int64_t t0, t1;
+    if (p.fixed_split_tiles > 0) {
+        t0 = (int64_t)it.j * p.fixed_split_tiles;
+        t1 = t0 + p.fixed_split_tiles;
+        t0 = t0 < nt ? t0 : nt;
+        t1 = t1 < nt ? t1 : nt;
+    } else {
+        t0 = (int64_t)it.j * nt / it.ns;
+        t1 = ((int64_t)it.j + 1) * nt / it.ns;
+    }
+    it.c0 = (int)t0 * SUB;
+    it.c1 = (int)t1 * SUB;
+    return it;
+}
+
+// Fills lim and off of a chunk whose (c, blk, cib) are set.  Reads one block-table entry; a block id
+// outside the pool is reported through err_flag and the chunk is treated as empty.
+template <int CH>
+__device__ __forceinline__ void locate_chunk(const MicroParams &p, const ItemInfo &it, Chunk &ch, int lane)
+{
+    ch.lim = 0;
+    ch.off = 0;
+    if (!ch.valid) return;
+    const int pb = table_load(p.block_table, (int64_t)it.r * p.max_blocks + ch.blk);
+    const int first = ch.cib * CH;
+    int valid = it.L - ch.blk * p.T;
+    valid = (valid > p.T ? p.T : valid) - first;
+    if ((unsigned)pb >= (unsigned)p.num_phys) {
+        if (lane == 0) atomicOr(p.err_flag, 1);
+        valid = 0;
+    }
+    ch.lim = valid;
+    if (valid > 0)
+        ch.off = (int64_t)pb * p.stride_block + (int64_t)it.kvh * p.stride_head + (int64_t)first * p.stride_token;
+}
+
+template <int CH>
+__device__ __forceinline__ Chunk first_chunk(const MicroParams &p, const ItemInfo &it, int wave, int lane)
+{
+    constexpr int SUB = kTile / CH;
+    const int cpb = ((p.T + kTile - 1) / kTile) * SUB;  // chunk slots per block
+    Chunk ch;
+    ch.c = it.c0 + wave;
+    ch.valid = it.valid && ch.c < it.c1;
+    ch.blk = ch.c / cpb;
+    ch.cib = ch.c - ch.blk * cpb;
+    locate_chunk<CH>(p, it, ch, lane);
+    return ch;
+}
+
+template <int CH, int W>
+__device__ __forceinline__ Chunk next_chunk(const MicroParams &p, const ItemInfo &it, Chunk ch, int lane)
+{
+    constexpr int SUB = kTile / CH;
+    const int cpb = ((p.T + kTile - 1) / kTile) * SUB;
+    ch.c += W;
+    ch.cib += W;
+    while (ch.cib >= cpb) {
+        ch.cib -= cpb;
+        ch.blk += 1;
+    }
+    ch.valid = ch.c < it.c1;
+    locate_chunk<CH>(p, it, ch, lane);
+    return ch;
+}
+
+}  // namespace da

@@ -4,12 +4,12 @@
 
 namespace da {
 
-constexpr int kHeadDim = 128;        // only head_dim supported
-constexpr int kWavesPerGroup = 8;    // MicroAttention workgroup = 8 wavefronts of 64 lanes
-constexpr int kThreads = kWavesPerGroup * 64;
+constexpr int kHeadDim = 128;    // only head_dim supported
+constexpr int kTile = 32;        // scheduling granule in tokens: splits begin and end on tiles of a block
 
-// One MicroAttention launch.  A work item (= one workgroup) is a (request, split, kv-head,
-// head tile): the split's KV blocks are read once and serve the head tile's q-heads.
+// One MicroAttention launch.  A work item is a (request, split, kv-head, head tile): the split's
+// tokens are read once and serve the head tile's q-heads.  The launch is persistent: workgroup b
+// handles items b, b + gridDim.x, ... (odd rounds mirrored) of the item list.
 struct MicroParams {
     const void *q;
     const void *k_pool;
@@ -27,12 +27,14 @@ struct MicroParams {
     const int64_t *row_base;     // [B] by request id: first partial row of the request
     int32_t *err_flag;
     int32_t B, Hq, Hkv, G, T, max_blocks, num_phys;
-    int32_t head_tile;   // q-heads served per work item
-    int32_t head_tiles;  // ceil(G / head_tile)
+    int32_t head_tile;          // q-heads served per work item
+    int32_t head_tiles;         // ceil(G / head_tile)
     int32_t q_bf16;
     int32_t direct_out;
+    int32_t num_items;
+    int32_t fixed_split_tiles;  // > 0: split j = tiles [j*f, (j+1)*f); 0: split j = tiles [j*nt/ns, (j+1)*nt/ns)
     int64_t stride_block, stride_head, stride_token;  // elements
-    float scale_log2e;   // scale * log2(e): scores are kept in base-2 units inside the kernel
+    float scale_log2e;          // scale * log2(e): scores are kept in base-2 units inside the kernels
 };
 
 struct CombineParams {

@@ -1,8 +1,11 @@
 // MicroAttention on the matrix cores, for grouped-query attention with bf16 q / K / V
 // (Section 4, m_j / e_j equation and Eq. 2; Section 3: the q-heads of a GQA group share one K/V read).
 //
-// One workgroup (8 wavefronts) owns one work item: a run of KV blocks of one (request, kv-head) and
-// a tile of up to 16 q-heads of its group.  Each wavefront walks 32-token chunks on its own:
+// A work item is a run of tokens of one (request, kv-head) and a tile of up to 16 q-heads of its
+// group.  The launch is persistent: each workgroup (4 wavefronts) walks its items one after the
+// other, and the first K chunk and the query of the next item are requested before the current
+// item's partial result is merged and written, so the memory pipe never drains between items.
+// Each wavefront walks 32-token chunks on its own:
 //
 //   S  = K  . Q^T   v_mfma_f32_16x16x32_bf16, A = 16 token rows of K (16 B of a row per lane, loaded
 //                   straight from HBM in operand layout), B = Q^T (head = lane % 16).  bf16 x bf16
@@ -16,6 +19,7 @@
 // Heads beyond the group (lanes with lane % 16 >= G) carry q = 0 and are never written.
 #include <hip/hip_runtime.h>
 
+#include "item_walk.h"
 #include "kernel_params.h"
 
 namespace da {
@@ -31,6 +35,7 @@ constexpr float kNegInf = -__builtin_inff();
 constexpr float kLn2 = 0.69314718055994530942f;
 constexpr int kHeadTile = 16;  // q-heads per work item (MFMA N dimension)
 constexpr int kChunk = 32;     // tokens per wavefront step (MFMA K dimension of the PV product)
+constexpr int kWaves = 4;      // wavefronts per workgroup
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
@@ -51,12 +56,12 @@ __device__ __forceinline__ f32x4 mfma_bf16(const u32x4 &a, const u32x4 &b, f32x4
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-__global__ __launch_bounds__(kThreads) void micro_attention_mfma_kernel(const MicroParams p)
+__global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const MicroParams p)
 {
-    // cross-wavefront merge buffers (live heads only are touched)
-    __shared__ float lds_m[kWavesPerGroup][kHeadTile];
-    __shared__ float lds_e[kWavesPerGroup][kHeadTile];
-    __shared__ float lds_o[kWavesPerGroup][kHeadTile][kHeadDim];
+    // cross-wavefront merge buffers, two sets used alternately by consecutive items
+    __shared__ float lds_m[2][kWaves][kHeadTile];
+    __shared__ float lds_e[2][kWaves][kHeadTile];
+    __shared__ float lds_o[2][kWaves][kHeadTile][kHeadDim];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -64,254 +69,219 @@ __global__ __launch_bounds__(kThreads) void micro_attention_mfma_kernel(const Mi
     const int lg = lane >> 4;   // lane group: k-slice of the MFMA operands
     const int ln = lane & 15;   // token row (K operand) / head (Q, P operands, results)
 
-    // ---- which work item -------------------------------------------------------------------
-    const int item = blockIdx.x;
-    int lo = 0, hi = p.B;
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (p.item_prefix[mid] <= item) lo = mid; else hi = mid;
-    }
-    const int r = p.order[lo];
-    const int local = item - p.item_prefix[lo];
-    const int ns = p.nsplits[r];
-    const int per_split = p.Hkv * p.head_tiles;
-    const int j = local / per_split;
-    const int rem = local - j * per_split;
-    const int kvh = rem / p.head_tiles;
-    const int ht = rem - kvh * p.head_tiles;
-
-    const int T = p.T;
-    int L = p.seq_lens[r];
-    L = L < 0 ? 0 : L;
-    const int64_t cap = (int64_t)p.max_blocks * T;
-    if ((int64_t)L > cap) L = (int)cap;
-    const int nb = (L + T - 1) / T;
-    const int b0 = (int)(((int64_t)j * nb) / ns);
-    const int b1 = (int)(((int64_t)(j + 1) * nb) / ns);
-
-    // ---- Q^T operand: head = ln, k-slice lg of each of the 4 k-steps -------------------------------
-    const int hl = ht * kHeadTile + ln;  // head inside the group
-    const bool live = hl < p.G;
-    u32x4 qreg[4];
-    {
-        const uint16_t *q = (const uint16_t *)p.q + ((int64_t)r * p.Hq + (int64_t)kvh * p.G + (live ? hl : 0)) * kHeadDim;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            qreg[ks] = *(const u32x4 *)(q + ks * 32 + lg * 8);
-            if (!live) qreg[ks] = u32x4{0u, 0u, 0u, 0u};
-        }
-    }
-    const float c2 = p.scale_log2e;
-
-    float m = kNegInf;   // running maximum of head ln's scores, base-2 units (all lane groups agree)
-    float e = 0.0f;      // this lane's share of the exp-sum (its 8 tokens per chunk)
-    f32x4 acc[8];        // O^T: acc[n][i] = O[head ln][column 32*lg + 8*i + n]
-#pragma unroll
-    for (int n = 0; n < 8; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // ---- chunk walk -----------------------------------------------------------------------------
-    const int cpb = (T + kChunk - 1) / kChunk;
-    const int nchunks = (b1 - b0) * cpb;
     const char *kbase = (const char *)p.k_pool;
     const char *vbase = (const char *)p.v_pool;
-    const int64_t row_bytes = p.stride_token * 2;
+    const uint32_t row_bytes = (uint32_t)p.stride_token * 2u;
     // K: lane reads token (16*mb + ln), bytes [64*ks + 16*lg, +16) of the row
-    const int64_t k_lane_off = (int64_t)ln * row_bytes + lg * 16;
+    const uint32_t k_lane_off = (uint32_t)ln * row_bytes + lg * 16;
     // V: lane reads token (16*(jj/4) + 4*lg + jj%4), bytes [16*ln, +16) of the row
-    const int64_t v_lane_off = (int64_t)(4 * lg) * row_bytes + ln * 16;
+    const uint32_t v_lane_off = (uint32_t)(4 * lg) * row_bytes + ln * 16;
+    const float c2 = p.scale_log2e;
 
-    struct Chunk {
-        int n, blk, cib;
-        int lim;       // valid tokens from the chunk's first row on (<= 0: none)
-        int64_t off;   // byte offset of the chunk's first row in a pool
-    };
-    auto locate = [&](Chunk &c) {
-        c.lim = 0;
-        c.off = 0;
-        if (c.n >= nchunks) return;
-        const int pb = p.block_table[(int64_t)r * p.max_blocks + c.blk];
-        const int first = c.cib * kChunk;
-        int valid = L - c.blk * T;
-        valid = (valid > T ? T : valid) - first;
-        if ((unsigned)pb >= (unsigned)p.num_phys) {
-            if (lane == 0) atomicOr(p.err_flag, 1);
-            valid = 0;
-        }
-        c.lim = valid;
-        c.off = ((int64_t)pb * p.stride_block + (int64_t)kvh * p.stride_head + (int64_t)first * p.stride_token) * 2;
-    };
-    auto advance = [&](Chunk c) {
-        c.n += kWavesPerGroup;
-        c.cib += kWavesPerGroup;
-        while (c.cib >= cpb) {
-            c.cib -= cpb;
-            c.blk += 1;
-        }
-        locate(c);
-        return c;
-    };
-    auto load_k = [&](const Chunk &c, u32x4 (&dst)[8]) {
+    // Every step issues 8 K loads and 8 V loads whatever the chunk: rows past the valid ones re-read
+    // the last valid row (their scores are masked), so the loads need no branches.
+    const uint32_t k_full[2] = {k_lane_off, k_lane_off + 16u * row_bytes};
+    uint32_t v_full[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) v_full[jj] = v_lane_off + (uint32_t)(16 * (jj >> 2) + (jj & 3)) * row_bytes;
+    auto load_k = [&](const Fetch &f, u32x4 (&dst)[8]) {
+        const char *base = kbase + f.off * 2;
+        const uint32_t clamp_off = (uint32_t)f.last * row_bytes + lg * 16;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
-            const bool ok = mb * 16 + ln < c.lim;
-            const char *row = kbase + c.off + k_lane_off + (int64_t)(mb * 16) * row_bytes;
+            const uint32_t off = k_full[mb] < clamp_off ? k_full[mb] : clamp_off;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                dst[mb * 4 + ks] = u32x4{0u, 0u, 0u, 0u};
-                if (ok) dst[mb * 4 + ks] = load16_stream(row + ks * 64);
-            }
+            for (int ks = 0; ks < 4; ++ks) dst[mb * 4 + ks] = load16_stream(base + off + ks * 64);
         }
     };
-    auto load_v = [&](const Chunk &c, u32x4 (&dst)[8]) {
+    auto load_v = [&](const Fetch &f, u32x4 (&dst)[8]) {
+        const char *base = vbase + f.off * 2;
+        const uint32_t clamp_off = (uint32_t)f.last * row_bytes + ln * 16;
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
-            const int tok = 16 * (jj >> 2) + (jj & 3);  // + 4*lg, folded into v_lane_off
-            dst[jj] = u32x4{0u, 0u, 0u, 0u};
-            if (tok + 4 * lg < c.lim) dst[jj] = load16_stream(vbase + c.off + v_lane_off + (int64_t)tok * row_bytes);
+            const uint32_t off = v_full[jj] < clamp_off ? v_full[jj] : clamp_off;
+            dst[jj] = load16_stream(base + off);
+        }
+    };
+    // Q^T operand of an item: head = ln, k-slice lg of each of the 4 k-steps (zero for heads past the group)
+    auto load_q = [&](const ItemInfo &it, u32x4 (&dst)[4]) {
+        const int hl = it.ht * kHeadTile + ln;
+        const bool live = it.valid && hl < p.G;
+        const uint16_t *q = (const uint16_t *)p.q + ((int64_t)it.r * p.Hq + (int64_t)it.kvh * p.G + (live ? hl : 0)) * kHeadDim;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            dst[ks] = u32x4{0u, 0u, 0u, 0u};
+            if (live) dst[ks] = *(const u32x4 *)(q + ks * 32 + lg * 8);
         }
     };
 
-    Chunk cur;
-    cur.n = wave;
-    cur.blk = b0 + wave / cpb;
-    cur.cib = wave % cpb;
-    locate(cur);
+    int round = 0;
+    ItemInfo it = decode_item<kChunk>(p, item_of(blockIdx.x, 0, gridDim.x));
+    Chunk cur = first_chunk<kChunk>(p, it, wave, lane);
+    u32x4 kr[8], vr[8], qreg[4];
+    load_k(fetch_of(cur), kr);
+    load_q(it, qreg);
 
-    u32x4 kr[8], vr[8];
-    if (cur.n < nchunks) load_k(cur, kr);
+    while (it.valid) {
+        float m = kNegInf;   // running maximum of head ln's scores, base-2 units (all lane groups agree)
+        float e = 0.0f;      // this lane's share of the exp-sum (its 8 tokens per chunk)
+        f32x4 acc[8];        // O^T: acc[n][i] = O[head ln][column 32*lg + 8*i + n]
+#pragma unroll
+        for (int n = 0; n < 8; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    while (cur.n < nchunks) {
-        load_v(cur, vr);
-        const Chunk nxt = advance(cur);
+        // the item after this one is looked up early, so that its first K chunk can be requested
+        // before this item's result is merged
+        const int buf = round & 1;
+        ++round;
+        const ItemInfo nit = decode_item<kChunk>(p, item_of(blockIdx.x, round, gridDim.x));
+        const Chunk ncur = first_chunk<kChunk>(p, nit, wave, lane);
 
-        // S[token 16*mb + 4*lg + i][head ln] for mb = 0, 1
-        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            s0 = mfma_bf16(kr[ks], qreg[ks], s0);
-            s1 = mfma_bf16(kr[4 + ks], qreg[ks], s1);
-        }
-        if (nxt.n < nchunks) load_k(nxt, kr);
+        // every step issues 8 V loads and 8 K loads; kr always holds the K rows of `cur`
+        const bool idle = !cur.valid;  // this wavefront has no chunk in the item
+        while (cur.valid) {
+            load_v(fetch_of(cur), vr);
+            const Chunk nxt = next_chunk<kChunk, kWaves>(p, it, cur, lane);
+            const Fetch kf_next = fetch_of(nxt.valid ? nxt : ncur);  // nothing left at all: row 0 of the pool
 
-        // scores in base-2 units (scale * log2(e) applied), rows past the valid tokens masked out
-        float s[8];
+            // S[token 16*mb + 4*lg + i][head ln] for mb = 0, 1
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            s[i] = (4 * lg + i < cur.lim) ? s0[i] * c2 : kNegInf;
-            s[4 + i] = (16 + 4 * lg + i < cur.lim) ? s1[i] * c2 : kNegInf;
-        }
-        float cm = s[0];
-#pragma unroll
-        for (int i = 1; i < 8; ++i) cm = fmaxf(cm, s[i]);
-        cm = fmaxf(cm, __shfl_xor(cm, 16));
-        cm = fmaxf(cm, __shfl_xor(cm, 32));
-        const float mn = fmaxf(m, cm);
-        const float mu = (mn == kNegInf) ? 0.0f : mn;
-        const float alpha = fast_exp2(m - mu);
-        m = mn;
-        float sum = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            s[i] = fast_exp2(s[i] - mu);
-            sum += s[i];
-        }
-        e = fmaf(e, alpha, sum);
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-            for (int n = 0; n < 8; ++n) acc[n] *= alpha;
-        }
-
-        // P^T operand: 8 tokens of this lane group, head ln; high and low bf16 parts
-        u32x4 ph, pl;
-        {
-            uint32_t h[4], l[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                h[t] = pack_bf16(s[2 * t], s[2 * t + 1]);
-                const float r0 = s[2 * t] - as_f(h[t] << 16);
-                const float r1 = s[2 * t + 1] - as_f(h[t] & 0xFFFF0000u);
-                l[t] = pack_bf16(r0, r1);
+            for (int ks = 0; ks < 4; ++ks) {
+                s0 = mfma_bf16(kr[ks], qreg[ks], s0);
+                s1 = mfma_bf16(kr[4 + ks], qreg[ks], s1);
             }
-            ph = u32x4{h[0], h[1], h[2], h[3]};
-            pl = u32x4{l[0], l[1], l[2], l[3]};
-        }
+            load_k(kf_next, kr);
+            if (cur.lim <= 0) {  // a chunk slot without valid tokens contributes nothing
+                cur = nxt;
+                continue;
+            }
 
-        // O^T += V^T . P^T, 8 MFMA column groups; column group n takes columns 8*m + n, m = MFMA row
+            // scores in base-2 units (scale * log2(e) applied), rows past the valid tokens masked out
+            float s[8];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const uint32_t d0 = vr[0][w], d1 = vr[1][w], d2 = vr[2][w], d3 = vr[3][w];
-            const uint32_t d4 = vr[4][w], d5 = vr[5][w], d6 = vr[6][w], d7 = vr[7][w];
-            // even column 2w: low halves; odd column 2w+1: high halves; (token 2t, token 2t+1) per register
-            const u32x4 ve = u32x4{__builtin_amdgcn_perm(d1, d0, 0x05040100u), __builtin_amdgcn_perm(d3, d2, 0x05040100u),
-                                        __builtin_amdgcn_perm(d5, d4, 0x05040100u), __builtin_amdgcn_perm(d7, d6, 0x05040100u)};
-            const u32x4 vo = u32x4{__builtin_amdgcn_perm(d1, d0, 0x07060302u), __builtin_amdgcn_perm(d3, d2, 0x07060302u),
-                                        __builtin_amdgcn_perm(d5, d4, 0x07060302u), __builtin_amdgcn_perm(d7, d6, 0x07060302u)};
-            acc[2 * w] = mfma_bf16(ve, ph, acc[2 * w]);
-            acc[2 * w] = mfma_bf16(ve, pl, acc[2 * w]);
-            acc[2 * w + 1] = mfma_bf16(vo, ph, acc[2 * w + 1]);
-            acc[2 * w + 1] = mfma_bf16(vo, pl, acc[2 * w + 1]);
-        }
-        cur = nxt;
-    }
+            for (int i = 0; i < 4; ++i) {
+                s[i] = (4 * lg + i < cur.lim) ? s0[i] * c2 : kNegInf;
+                s[4 + i] = (16 + 4 * lg + i < cur.lim) ? s1[i] * c2 : kNegInf;
+            }
+            float cm = s[0];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) cm = fmaxf(cm, s[i]);
+            cm = fmaxf(cm, __shfl_xor(cm, 16));
+            cm = fmaxf(cm, __shfl_xor(cm, 32));
+            const float mn = fmaxf(m, cm);
+            const float mu = (mn == kNegInf) ? 0.0f : mn;
+            const float alpha = fast_exp2(m - mu);
+            m = mn;
+            float sum = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                s[i] = fast_exp2(s[i] - mu);
+                sum += s[i];
+            }
+            e = fmaf(e, alpha, sum);
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                for (int n = 0; n < 8; ++n) acc[n] *= alpha;
+            }
 
-    // ---- wavefront result: exp-sum over the lane groups; m is already common ---------------------
-    e += __shfl_xor(e, 16);
-    e += __shfl_xor(e, 32);
-    if (live) {
-        if (lg == 0) {
-            lds_m[wave][ln] = m;
-            lds_e[wave][ln] = e;
-        }
+            // P^T operand: 8 tokens of this lane group, head ln; high and low bf16 parts
+            u32x4 ph, pl;
+            {
+                uint32_t h[4], l[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float *dst = &lds_o[wave][ln][32 * lg + 8 * i];
-            *(float4 *)dst = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
-            *(float4 *)(dst + 4) = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
-        }
-    }
-    __syncthreads();
+                for (int t = 0; t < 4; ++t) {
+                    h[t] = pack_bf16(s[2 * t], s[2 * t + 1]);
+                    const float r0 = s[2 * t] - as_f(h[t] << 16);
+                    const float r1 = s[2 * t + 1] - as_f(h[t] & 0xFFFF0000u);
+                    l[t] = pack_bf16(r0, r1);
+                }
+                ph = u32x4{h[0], h[1], h[2], h[3]};
+                pl = u32x4{l[0], l[1], l[2], l[3]};
+            }
 
-    // ---- merge the wavefronts and write the item's result -----------------------------------------
-    const bool direct = p.direct_out && ns == 1;
-    int heads = p.G - ht * kHeadTile;
-    heads = heads > kHeadTile ? kHeadTile : heads;
-    for (int idx = tid; idx < heads * kHeadDim; idx += kThreads) {
-        const int g = idx / kHeadDim, col = idx % kHeadDim;
-        float M = lds_m[0][g];
+            // O^T += V^T . P^T, 8 MFMA column groups; column group n takes columns 8*m + n, m = MFMA row
 #pragma unroll
-        for (int w = 1; w < kWavesPerGroup; ++w) M = fmaxf(M, lds_m[w][g]);
-        const float mu = (M == kNegInf) ? 0.0f : M;
-        float o = 0.0f, E = 0.0f;
-#pragma unroll
-        for (int w = 0; w < kWavesPerGroup; ++w) {
-            const float wgt = fast_exp2(lds_m[w][g] - mu);
-            o = fmaf(lds_o[w][g][col], wgt, o);
-            E = fmaf(lds_e[w][g], wgt, E);
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t d0 = vr[0][w], d1 = vr[1][w], d2 = vr[2][w], d3 = vr[3][w];
+                const uint32_t d4 = vr[4][w], d5 = vr[5][w], d6 = vr[6][w], d7 = vr[7][w];
+                // even column 2w: low halves; odd column 2w+1: high halves; (token 2t, token 2t+1) per register
+                const u32x4 ve = u32x4{__builtin_amdgcn_perm(d1, d0, 0x05040100u), __builtin_amdgcn_perm(d3, d2, 0x05040100u),
+                                       __builtin_amdgcn_perm(d5, d4, 0x05040100u), __builtin_amdgcn_perm(d7, d6, 0x05040100u)};
+                const u32x4 vo = u32x4{__builtin_amdgcn_perm(d1, d0, 0x07060302u), __builtin_amdgcn_perm(d3, d2, 0x07060302u),
+                                       __builtin_amdgcn_perm(d5, d4, 0x07060302u), __builtin_amdgcn_perm(d7, d6, 0x07060302u)};
+                acc[2 * w] = mfma_bf16(ve, ph, acc[2 * w]);
+                acc[2 * w] = mfma_bf16(ve, pl, acc[2 * w]);
+                acc[2 * w + 1] = mfma_bf16(vo, ph, acc[2 * w + 1]);
+                acc[2 * w + 1] = mfma_bf16(vo, pl, acc[2 * w + 1]);
+            }
+            cur = nxt;
         }
-        const int h = kvh * p.G + ht * kHeadTile + g;
-        const float m_nat = M * kLn2;  // base-2 -> natural-log score units (-inf stays -inf)
-        if (direct) {
-            const int64_t orow = (int64_t)r * p.Hq + h;
-            p.out[orow * kHeadDim + col] = (E > 0.0f) ? o / E : 0.0f;
-            if (col == 0 && p.lse) p.lse[orow] = (E > 0.0f) ? m_nat + __logf(E) : kNegInf;
-        } else {
-            const int64_t prow = p.row_base[r] + (int64_t)h * ns + j;
-            p.part_o[prow * kHeadDim + col] = o;
-            if (col == 0) {
-                p.part_m[prow] = m_nat;
-                p.part_e[prow] = E;
+        // the last step above requested the first K chunk of the next item
+        if (idle) load_k(fetch_of(ncur), kr);
+        load_q(nit, qreg);
+
+        // ---- wavefront result: exp-sum over the lane groups; m is already common -----------------
+        const int hl = it.ht * kHeadTile + ln;
+        e += __shfl_xor(e, 16);
+        e += __shfl_xor(e, 32);
+        if (hl < p.G) {
+            if (lg == 0) {
+                lds_m[buf][wave][ln] = m;
+                lds_e[buf][wave][ln] = e;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float *dst = &lds_o[buf][wave][ln][32 * lg + 8 * i];
+                *(float4 *)dst = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
+                *(float4 *)(dst + 4) = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
             }
         }
+        __syncthreads();
+
+        // ---- merge the wavefronts and write the item's result -------------------------------------
+        const bool direct = p.direct_out && it.ns == 1;
+        int heads = p.G - it.ht * kHeadTile;
+        heads = heads > kHeadTile ? kHeadTile : heads;
+        for (int idx = tid; idx < heads * kHeadDim; idx += kWaves * 64) {
+            const int g = idx / kHeadDim, col = idx % kHeadDim;
+            float M = lds_m[buf][0][g];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) M = fmaxf(M, lds_m[buf][w][g]);
+            const float mu = (M == kNegInf) ? 0.0f : M;
+            float o = 0.0f, E = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const float wgt = fast_exp2(lds_m[buf][w][g] - mu);
+                o = fmaf(lds_o[buf][w][g][col], wgt, o);
+                E = fmaf(lds_e[buf][w][g], wgt, E);
+            }
+            const int h = it.kvh * p.G + it.ht * kHeadTile + g;
+            const float m_nat = M * kLn2;  // base-2 -> natural-log score units (-inf stays -inf)
+            if (direct) {
+                const int64_t orow = (int64_t)it.r * p.Hq + h;
+                p.out[orow * kHeadDim + col] = (E > 0.0f) ? o / E : 0.0f;
+                if (col == 0 && p.lse) p.lse[orow] = (E > 0.0f) ? m_nat + __logf(E) : kNegInf;
+            } else {
+                const int64_t prow = it.row_base + (int64_t)h * it.ns + it.j;
+                p.part_o[prow * kHeadDim + col] = o;
+                if (col == 0) {
+                    p.part_m[prow] = m_nat;
+                    p.part_e[prow] = E;
+                }
+            }
+        }
+        it = nit;
+        cur = ncur;
     }
 }
 
 }  // namespace
 
-hipError_t launch_micro_attention_mfma(const MicroParams &p, int64_t num_items, hipStream_t stream)
+hipError_t launch_micro_attention_mfma(const MicroParams &p, int grid, hipStream_t stream)
 {
-    if (num_items <= 0) return hipSuccess;
-    if (p.head_tile != kHeadTile || !p.q_bf16) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(micro_attention_mfma_kernel, dim3((unsigned)num_items), dim3(kThreads), 0, stream, p);
+    if (p.num_items <= 0) return hipSuccess;
+    if (p.head_tile != kHeadTile || !p.q_bf16 || grid < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(micro_attention_mfma_kernel, dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -61,7 +61,7 @@ def lib():
         L.da_plan_update.argtypes = [vp, vp, vp]
         L.da_plan_destroy.argtypes = [vp]
         L.da_plan_num_partials.argtypes = [vp, i64p]
-        L.da_plan_split.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, i32p, i32p]
+        L.da_plan_split.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, i64p, i64p]
         L.da_plan_nsplits.argtypes = [vp, ctypes.c_int32, i32p]
         L.da_workspace_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
         L.da_plan_error.argtypes = [vp, vp, i32p]
@@ -184,7 +184,7 @@ class Plan:
         return n.value
 
     def split(self, r, j):
-        a, b = ctypes.c_int32(), ctypes.c_int32()
+        a, b = ctypes.c_int64(), ctypes.c_int64()
         _check(lib().da_plan_split(self._h, r, j, ctypes.byref(a), ctypes.byref(b)), "da_plan_split")
         return a.value, b.value
 

@@ -44,7 +44,7 @@ def test_scaled_workloads_match_oracle(name, div, over, kernel):
 
 
 # ------------------------------------------------------------------ raw partials, Eq. 2 literally
-@pytest.mark.parametrize("bps", [1, 3])
+@pytest.mark.parametrize("bps", [0, 1, 3])
 @pytest.mark.parametrize("name,div", [("c1_tiny", 1), ("c5_mixed", 200), ("c3_70b", 128)])
 @pytest.mark.parametrize("kernel", [da.DA_KERNEL_AUTO, da.DA_KERNEL_VALU], ids=["auto", "valu"])
 def test_partials_match_micro_attention(name, div, bps, kernel):
@@ -60,9 +60,12 @@ def test_partials_match_micro_attention(name, div, bps, kernel):
         L = int(w["seq_lens_host"][r])
         b = [0]
         for j in range(plan.nsplits(r)):
-            first, n = plan.split(r, j)
-            assert first * T == b[-1] or L == 0 or n == 0
-            b.append(min(L, (first + n) * T))
+            lo, hi = plan.split(r, j)
+            assert lo == b[-1] and lo <= hi <= L
+            if bps > 0 and L > 0:
+                assert lo == min(L, j * bps * T) and hi == min(L, (j + 1) * bps * T)  # whole blocks, as asked
+            b.append(hi)
+        assert b[-1] == L
         bounds.append(b)
     h = oracle_inputs(w)
     MA, m, e, nparts = oracle.micro_attention(h["q"], h["k_pool"], h["v_pool"], h["block_table"], h["seq_lens"],

@@ -170,7 +170,8 @@ def main():
         "config": {"workload": w["name"], "batch": w["B"], "q_heads": w["Hq"], "kv_heads": w["Hkv"], "head_dim": 128,
                    "block_tokens": w["T"], "tokens_total": int(w["seq_lens_host"].sum()),
                    "max_len": int(w["seq_lens_host"].max()), "kv_bytes": int(kv_bytes),
-                   "work_items": sched["num_items"], "partials": sched["num_partials"], "kernel": sched["kernel"]},
+                   "work_items": sched["num_items"], "workgroups": sched["workgroups"], "partials": sched["num_partials"],
+                   "kernel": sched["kernel"]},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "decode_tokens_per_s_per_layer": round(w["B"] / (ms_per_step * 1e-3), 1),
         "fused_da_attention_ms": round(fused_ms, 4),

@@ -102,32 +102,36 @@ typedef struct da_plan da_plan; /* opaque: split schedule of one batch + its sma
 /*
  * Work scheduling (host).  Section 5.3, Eq. 5 prices attention by total KV
  * length, not batch size; Section 3 allows partitions of any length.  The
- * plan therefore cuts every request's tokens into nsplits[r] near-equal runs
- * ("splits"), each starting and ending on a 32-token tile of a block and of
- * about the same size across the whole batch, so that the (split, kv-head)
- * work items keep every compute unit equally busy, from one short request to
- * one 2M-token request.  With da_tuning.blocks_per_split > 0 every split is
- * exactly that many blocks instead.
+ * plan lays the 32-token tiles of all requests end to end (longest request
+ * first) and cuts that stream into runs of equal cost, one run per persistent
+ * workgroup and kv-head; a cut that falls inside a request splits it there.
+ * Every workgroup of the MicroAttention launch therefore reads the same number
+ * of bytes, from one short request to one 2M-token request, and no request is
+ * split more than that balance needs (nsplits[r] >= 1).  With
+ * da_tuning.blocks_per_split > 0 every split is exactly that many blocks
+ * instead, and whole splits are dealt to the workgroups.
  *
- * da_plan_schedule: pure host arithmetic, no HIP call.  Writes nsplits[r]
- *   (>= 1; 1 for an empty request) into nsplits_host[batch] and the processing
- *   order (request ids, longest first) into order_host[batch]; either may be
- *   NULL.  *num_items = work items of the MicroAttention launch, *num_partials
- *   = rows of part_*, *kernel = the da_kernel chosen.
+ * da_plan_schedule: pure host arithmetic, no HIP call.  Writes nsplits[r] into
+ *   nsplits_host[batch] (may be NULL).  *num_items = (split, kv-head) work
+ *   items, *num_partials = rows of part_*, *kernel = the da_kernel chosen,
+ *   *workgroups = size of the MicroAttention launch, *max_workgroup_tokens =
+ *   the most tokens any one workgroup reads (any may be NULL).
  * da_plan_create: the same schedule, plus its device tables.  seq_lens_host is
  *   read during the call and not retained.  Destroy with da_plan_destroy.
- * da_plan_update: re-plan the same problem for new lengths in place (no
- *   allocation unless the batch grew beyond the created capacity, which is an
- *   error).  Ordered on `stream` after earlier launches that used the plan.
+ * da_plan_update: re-plan the same problem for new lengths in place.  Ordered
+ *   on `stream` after earlier launches that used the plan; allocates (and
+ *   waits for `stream`) only if the split table outgrew its capacity.
  * The lengths given here must equal the device seq_lens passed to the launch
- * calls; the device values decide which tokens are read, the host values only
- * how the work is cut.
+ * calls: the host values decide how the work is cut, the device values where
+ * each request's valid tokens end.
+ * A plan serves one launch at a time per stream order; it is not to be used
+ * from two host threads at once.
  * Errors: DA_ERR_INVALID_ARG / DA_ERR_UNSUPPORTED from validation (before any
  * HIP call), DA_ERR_HIP if the device tables cannot be made.
  */
 da_status da_plan_schedule(const da_problem *problem, const int32_t *seq_lens_host, const da_tuning *tuning,
-                           int32_t *nsplits_host, int32_t *order_host, int64_t *num_items,
-                           int64_t *num_partials, int32_t *kernel);
+                           int32_t *nsplits_host, int64_t *num_items, int64_t *num_partials, int32_t *kernel,
+                           int32_t *workgroups, int64_t *max_workgroup_tokens);
 da_status da_plan_create(const da_problem *problem, const int32_t *seq_lens_host, const da_tuning *tuning,
                          void *stream, da_plan **plan);
 da_status da_plan_update(da_plan *plan, const int32_t *seq_lens_host, void *stream);

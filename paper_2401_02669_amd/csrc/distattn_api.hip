@@ -21,17 +21,18 @@ constexpr int kRing = 4;  // pinned staging slots for table uploads
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Device tables of a plan: [entries | range_start | nsplits | row_base | error flag], sized for a capacity.
 struct TableLayout {
-    size_t order, item_prefix, nsplits, row_base, err, total;
-    explicit TableLayout(int B)
+    size_t entries, range_start, nsplits, row_base, err, total;
+    TableLayout(size_t cap_entries, size_t cap_ranges, size_t batch)
     {
         size_t off = 0;
-        order = off;       off = align_up(off + sizeof(int32_t) * B, 16);
-        item_prefix = off; off = align_up(off + sizeof(int32_t) * (B + 1), 16);
-        nsplits = off;     off = align_up(off + sizeof(int32_t) * B, 16);
-        row_base = off;    off = align_up(off + sizeof(int64_t) * B, 16);
+        entries = off;     off = align_up(off + sizeof(da::SplitEntry) * cap_entries, 32);
+        range_start = off; off = align_up(off + sizeof(int32_t) * (cap_ranges + 1), 32);
+        nsplits = off;     off = align_up(off + sizeof(int32_t) * batch, 32);
+        row_base = off;    off = align_up(off + sizeof(int64_t) * batch, 32);
         total = off;  // uploaded part
-        err = off;    off = align_up(off + sizeof(int32_t), 16);
+        err = off;    off = align_up(off + sizeof(int32_t), 32);
     }
 };
 
@@ -41,11 +42,10 @@ struct da_plan {
     da_problem problem;
     da_tuning tuning;
     int32_t num_cus;
-    int device;
     da::Schedule sched;
     std::vector<int32_t> lens;  // host lengths the schedule was made from
+    size_t cap_entries = 0, cap_ranges = 0;
     char *dev = nullptr;       // device tables (+ error flag at layout.err)
-    size_t dev_bytes = 0;
     char *stage[kRing] = {};   // pinned host staging
     hipEvent_t ev[kRing] = {};
     bool ev_pending[kRing] = {};
@@ -54,10 +54,42 @@ struct da_plan {
 
 namespace {
 
+TableLayout layout_of(const da_plan *pl) { return TableLayout(pl->cap_entries, pl->cap_ranges, pl->problem.batch); }
+
+void release_tables(da_plan *pl)
+{
+    for (int i = 0; i < kRing; ++i) {
+        if (pl->ev_pending[i]) (void)hipEventSynchronize(pl->ev[i]);
+        pl->ev_pending[i] = false;
+        if (pl->stage[i]) (void)hipHostFree(pl->stage[i]);
+        pl->stage[i] = nullptr;
+    }
+    if (pl->dev) (void)hipFree(pl->dev);
+    pl->dev = nullptr;
+}
+
+// (Re)allocates the tables so that the current schedule fits, with room to grow.
+da_status reserve_tables(da_plan *pl, hipStream_t stream)
+{
+    const size_t need_e = pl->sched.entries.size(), need_r = (size_t)pl->sched.ranges;
+    if (pl->dev && need_e <= pl->cap_entries && need_r <= pl->cap_ranges) return DA_OK;
+    if (pl->dev && hipStreamSynchronize(stream) != hipSuccess) return DA_ERR_HIP;  // earlier launches still read them
+    release_tables(pl);
+    pl->cap_entries = need_e * 2 + 1024;
+    pl->cap_ranges = std::max<size_t>(need_r * 2, 1024);
+    const TableLayout lay = layout_of(pl);
+    bool ok = hipMalloc((void **)&pl->dev, lay.err + 32) == hipSuccess;
+    for (int i = 0; ok && i < kRing; ++i) ok = hipHostMalloc((void **)&pl->stage[i], lay.total, hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipMemsetAsync(pl->dev + lay.err, 0, 32, stream) == hipSuccess;
+    return ok ? DA_OK : DA_ERR_HIP;
+}
+
 da_status upload(da_plan *pl, hipStream_t stream)
 {
+    da_status st = reserve_tables(pl, stream);
+    if (st != DA_OK) return st;
     const int B = pl->problem.batch;
-    const TableLayout lay(B);
+    const TableLayout lay = layout_of(pl);
     const int slot = pl->ring;
     pl->ring = (pl->ring + 1) % kRing;
     if (pl->ev_pending[slot]) {
@@ -65,11 +97,17 @@ da_status upload(da_plan *pl, hipStream_t stream)
         pl->ev_pending[slot] = false;
     }
     char *h = pl->stage[slot];
-    std::memcpy(h + lay.order, pl->sched.order.data(), sizeof(int32_t) * B);
-    std::memcpy(h + lay.item_prefix, pl->sched.item_prefix.data(), sizeof(int32_t) * (B + 1));
-    std::memcpy(h + lay.nsplits, pl->sched.nsplits.data(), sizeof(int32_t) * B);
-    std::memcpy(h + lay.row_base, pl->sched.row_base.data(), sizeof(int64_t) * B);
-    if (hipMemcpyAsync(pl->dev, h, lay.total, hipMemcpyHostToDevice, stream) != hipSuccess) return DA_ERR_HIP;
+    const da::Schedule &s = pl->sched;
+    std::memcpy(h + lay.entries, s.entries.data(), sizeof(da::SplitEntry) * s.entries.size());
+    std::memcpy(h + lay.range_start, s.range_start.data(), sizeof(int32_t) * s.range_start.size());
+    std::memcpy(h + lay.nsplits, s.nsplits.data(), sizeof(int32_t) * B);
+    std::memcpy(h + lay.row_base, s.row_base.data(), sizeof(int64_t) * B);
+    // two copies: the used part of the entry table, and the three small tables behind it
+    const size_t used_entries = sizeof(da::SplitEntry) * s.entries.size();
+    if (hipMemcpyAsync(pl->dev + lay.entries, h + lay.entries, used_entries, hipMemcpyHostToDevice, stream) != hipSuccess ||
+        hipMemcpyAsync(pl->dev + lay.range_start, h + lay.range_start, lay.total - lay.range_start, hipMemcpyHostToDevice,
+                       stream) != hipSuccess)
+        return DA_ERR_HIP;
     if (hipEventRecord(pl->ev[slot], stream) != hipSuccess) return DA_ERR_HIP;
     pl->ev_pending[slot] = true;
     return DA_OK;
@@ -78,11 +116,9 @@ da_status upload(da_plan *pl, hipStream_t stream)
 void fill_micro(const da_plan *pl, da::MicroParams &mp)
 {
     const da_problem &p = pl->problem;
-    const TableLayout lay(p.batch);
-    mp.order = (const int32_t *)(pl->dev + lay.order);
-    mp.item_prefix = (const int32_t *)(pl->dev + lay.item_prefix);
-    mp.nsplits = (const int32_t *)(pl->dev + lay.nsplits);
-    mp.row_base = (const int64_t *)(pl->dev + lay.row_base);
+    const TableLayout lay = layout_of(pl);
+    mp.entries = (const da::SplitEntry *)(pl->dev + lay.entries);
+    mp.range_start = (const int32_t *)(pl->dev + lay.range_start);
     mp.err_flag = (int32_t *)(pl->dev + lay.err);
     mp.B = p.batch;
     mp.Hq = p.num_q_heads;
@@ -93,9 +129,8 @@ void fill_micro(const da_plan *pl, da::MicroParams &mp)
     mp.num_phys = p.num_phys_blocks;
     mp.head_tile = pl->sched.head_tile;
     mp.head_tiles = pl->sched.head_tiles;
+    mp.per_split = p.num_kv_heads * pl->sched.head_tiles;
     mp.q_bf16 = p.q_dtype == DA_BF16;
-    mp.num_items = (int32_t)pl->sched.num_items;
-    mp.fixed_split_tiles = pl->sched.fixed_split_tiles;
     mp.stride_block = p.kv_block_stride;
     mp.stride_head = p.kv_head_stride;
     mp.stride_token = p.kv_token_stride;
@@ -114,7 +149,7 @@ da_status launch_micro(const da_plan *pl, const da::MicroParams &mp, hipStream_t
 
 void fill_combine(const da_plan *pl, da::CombineParams &cp)
 {
-    const TableLayout lay(pl->problem.batch);
+    const TableLayout lay = layout_of(pl);
     cp.nsplits = (const int32_t *)(pl->dev + lay.nsplits);
     cp.row_base = (const int64_t *)(pl->dev + lay.row_base);
     cp.B = pl->problem.batch;
@@ -141,8 +176,8 @@ const char *da_status_string(da_status s)
 }
 
 da_status da_plan_schedule(const da_problem *problem, const int32_t *seq_lens_host, const da_tuning *tuning,
-                           int32_t *nsplits_host, int32_t *order_host, int64_t *num_items, int64_t *num_partials,
-                           int32_t *kernel)
+                           int32_t *nsplits_host, int64_t *num_items, int64_t *num_partials, int32_t *kernel,
+                           int32_t *workgroups, int64_t *max_workgroup_tokens)
 {
     if (!problem || !seq_lens_host) return DA_ERR_INVALID_ARG;
     da_tuning t = {0, 0, 0};
@@ -152,10 +187,24 @@ da_status da_plan_schedule(const da_problem *problem, const int32_t *seq_lens_ho
     da_status st = da::make_schedule(*problem, seq_lens_host, t, t.num_cus > 0 ? t.num_cus : 256, s);
     if (st != DA_OK) return st;
     if (nsplits_host) std::memcpy(nsplits_host, s.nsplits.data(), sizeof(int32_t) * problem->batch);
-    if (order_host) std::memcpy(order_host, s.order.data(), sizeof(int32_t) * problem->batch);
     if (num_items) *num_items = s.num_items;
     if (num_partials) *num_partials = s.num_partials;
     if (kernel) *kernel = s.kernel;
+    if (workgroups) *workgroups = s.grid;
+    if (max_workgroup_tokens) {
+        int64_t worst = 0;
+        for (int m = 0; m < s.ranges; ++m) {
+            int64_t tok = 0;
+            for (int e = s.range_start[m]; e < s.range_start[m + 1]; ++e) {
+                const da::SplitEntry &en = s.entries[e];
+                const int64_t L = seq_lens_host[en.r];
+                tok += std::min<int64_t>(L, da::tile_first_token(en.t1, problem->block_tokens)) -
+                       std::min<int64_t>(L, da::tile_first_token(en.t0, problem->block_tokens));
+            }
+            worst = std::max(worst, tok);
+        }
+        *max_workgroup_tokens = worst;
+    }
     return DA_OK;
 }
 
@@ -184,23 +233,15 @@ da_status da_plan_create(const da_problem *problem, const int32_t *seq_lens_host
     pl->problem = *problem;
     pl->tuning = t;
     pl->num_cus = cus;
-    pl->device = device;
     st = da::make_schedule(pl->problem, seq_lens_host, t, cus, pl->sched);
-    if (st == DA_OK) pl->lens.assign(seq_lens_host, seq_lens_host + problem->batch);
     if (st != DA_OK) {
         delete pl;
         return st;
     }
-    const TableLayout lay(problem->batch);
-    pl->dev_bytes = lay.err + 16;
-    bool ok = hipMalloc((void **)&pl->dev, pl->dev_bytes) == hipSuccess;
-    for (int i = 0; ok && i < kRing; ++i) {
-        ok = hipHostMalloc((void **)&pl->stage[i], lay.total, hipHostMallocDefault) == hipSuccess &&
-             hipEventCreateWithFlags(&pl->ev[i], hipEventDisableTiming) == hipSuccess;
-    }
-    hipStream_t s = (hipStream_t)stream;
-    ok = ok && hipMemsetAsync(pl->dev + lay.err, 0, 16, s) == hipSuccess;
-    if (ok) ok = upload(pl, s) == DA_OK;
+    pl->lens.assign(seq_lens_host, seq_lens_host + problem->batch);
+    bool ok = true;
+    for (int i = 0; ok && i < kRing; ++i) ok = hipEventCreateWithFlags(&pl->ev[i], hipEventDisableTiming) == hipSuccess;
+    if (ok) ok = upload(pl, (hipStream_t)stream) == DA_OK;
     if (!ok) {
         da_plan_destroy(pl);
         return DA_ERR_HIP;
@@ -223,12 +264,9 @@ da_status da_plan_update(da_plan *pl, const int32_t *seq_lens_host, void *stream
 da_status da_plan_destroy(da_plan *pl)
 {
     if (!pl) return DA_OK;
-    for (int i = 0; i < kRing; ++i) {
-        if (pl->ev_pending[i]) (void)hipEventSynchronize(pl->ev[i]);
+    release_tables(pl);
+    for (int i = 0; i < kRing; ++i)
         if (pl->ev[i]) (void)hipEventDestroy(pl->ev[i]);
-        if (pl->stage[i]) (void)hipHostFree(pl->stage[i]);
-    }
-    if (pl->dev) (void)hipFree(pl->dev);
     delete pl;
     return DA_OK;
 }
@@ -250,15 +288,12 @@ da_status da_plan_nsplits(const da_plan *pl, int32_t r, int32_t *nsplits)
 da_status da_plan_split(const da_plan *pl, int32_t r, int32_t j, int64_t *first_token, int64_t *end_token)
 {
     if (!pl || !first_token || !end_token || r < 0 || r >= pl->problem.batch) return DA_ERR_INVALID_ARG;
-    const int32_t ns = pl->sched.nsplits[r];
-    if (j < 0 || j >= ns) return DA_ERR_INVALID_ARG;
-    // same cut as the kernels, in 32-token tiles of a block
-    int64_t t0, t1;
-    da::split_tiles(pl->sched.ntiles[r], ns, pl->sched.fixed_split_tiles, j, &t0, &t1);
+    if (j < 0 || j >= pl->sched.nsplits[r]) return DA_ERR_INVALID_ARG;
+    const da::SplitEntry &e = pl->sched.entries[pl->sched.first_entry[r] + j];
     const int32_t T = pl->problem.block_tokens;
     const int64_t L = pl->lens[r];
-    *first_token = std::min<int64_t>(L, da::tile_first_token(t0, T));
-    *end_token = std::min<int64_t>(L, da::tile_first_token(t1, T));
+    *first_token = std::min<int64_t>(L, da::tile_first_token(e.t0, T));
+    *end_token = std::min<int64_t>(L, da::tile_first_token(e.t1, T));
     return DA_OK;
 }
 
@@ -273,7 +308,7 @@ da_status da_workspace_bytes(const da_plan *pl, size_t *bytes)
 da_status da_plan_error(da_plan *pl, void *stream, int32_t *flags)
 {
     if (!pl || !flags) return DA_ERR_INVALID_ARG;
-    const TableLayout lay(pl->problem.batch);
+    const TableLayout lay = layout_of(pl);
     hipStream_t s = (hipStream_t)stream;
     int32_t v = 0;
     if (hipMemcpyAsync(&v, pl->dev + lay.err, sizeof v, hipMemcpyDeviceToHost, s) != hipSuccess) return DA_ERR_HIP;

@@ -1,7 +1,7 @@
 // Device-side walk over work items and their KV chunks, shared by the MicroAttention kernels.
 //
 // An item covers the tiles [t0, t1) of one request (tile = 32 tokens inside a block; a block holds
-// ceil(T / 32) tiles).  A kernel reads it in chunks of CH tokens (CH divides 32); wavefront w of W
+// ceil(T / 32) tiles) for one kv-head and head tile.  A kernel reads it in chunks of CH tokens (CH divides 32); wavefront w of W
 // takes chunks w, w + W, ... of the item.  Everything here is uniform across a wavefront.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -55,62 +55,43 @@ __device__ __forceinline__ Fetch fetch_of(const Chunk &c)
     return f;
 }
 
-// Item number handled by workgroup `b` in round `k` of a persistent grid of `g` workgroups: rounds
-// alternate direction so that no workgroup always gets the largest item of a size-sorted round.
-__device__ __forceinline__ int item_of(int b, int k, int g) { return k * g + ((k & 1) ? g - 1 - b : b); }
-
+// Split number `e` of the workgroup's run (valid while e < e_end), for kv-head kvh and head tile ht.
 template <int CH>
-__device__ __forceinline__ ItemInfo decode_item(const MicroParams &p, int item)
+__device__ __forceinline__ ItemInfo decode_item(const MicroParams &p, int e, int e_end, int kvh, int ht)
 {
     constexpr int SUB = kTile / CH;  // chunks per tile
     ItemInfo it;
-    it.valid = item < p.num_items;
-    it.r = it.j = it.kvh = it.ht = 0;
+    it.valid = e < e_end;
+    it.r = it.j = 0;
+    it.kvh = kvh;
+    it.ht = ht;
     it.ns = 1;
     it.L = 0;
     it.c0 = it.c1 = 0;
     it.row_base = 0;
     if (!it.valid) return it;
-    int lo = 0, hi = p.B;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (table_load(p.item_prefix, mid) <= item) lo = mid; else hi = mid;
-    }
-    it.r = table_load(p.order, lo);
-    const int local = item - table_load(p.item_prefix, lo);
-    it.ns = table_load(p.nsplits, it.r);
-    it.row_base = table_load(p.row_base, it.r);
-    const int per_split = p.Hkv * p.head_tiles;
-    it.j = local / per_split;
-    const int rem = local - it.j * per_split;
-    it.kvh = rem / p.head_tiles;
-    it.ht = rem - it.kvh * p.head_tiles;
-
-    const int T = p.T;
+    typedef const SplitEntry __attribute__((address_space(4))) * entry_ptr;
+    const entry_ptr ent = (entry_ptr)(uintptr_t)(p.entries + e);
+    it.r = ent->r;
+    it.j = ent->j;
+    it.ns = ent->ns;
+    it.row_base = ent->row_base;
+    it.c0 = ent->t0 * SUB;
+    it.c1 = ent->t1 * SUB;
     int L = table_load(p.seq_lens, it.r);
     L = L < 0 ? 0 : L;
-    const int64_t cap = (int64_t)p.max_blocks * T;
+    const int64_t cap = (int64_t)p.max_blocks * p.T;
     if ((int64_t)L > cap) L = (int)cap;
     it.L = L;
-    const int tpb = (T + kTile - 1) / kTile;
+    // never walk past the tiles the device length really has (the split table was made from host lengths)
+    const int tpb = (p.T + kTile - 1) / kTile;
     int nt = 0;
     if (L > 0) {
-        const int nb = (L + T - 1) / T;
-        const int tail = L - (nb - 1) * T;
-        nt = (nb - 1) * tpb + (tail + kTile - 1) / kTile;
+        const int nb = (L + p.T - 1) / p.T;
+        nt = (nb - 1) * tpb + (L - (nb - 1) * p.T + kTile - 1) / kTile;
     }
-    int64_t t0, t1;
-    if (p.fixed_split_tiles > 0) {
-        t0 = (int64_t)it.j * p.fixed_split_tiles;
-        t1 = t0 + p.fixed_split_tiles;
-        t0 = t0 < nt ? t0 : nt;
-        t1 = t1 < nt ? t1 : nt;
-    } else {
-        t0 = (int64_t)it.j * nt / it.ns;
-        t1 = ((int64_t)it.j + 1) * nt / it.ns;
-    }
-    it.c0 = (int)t0 * SUB;
-    it.c1 = (int)t1 * SUB;
+    if (it.c0 > nt * SUB) it.c0 = nt * SUB;
+    if (it.c1 > nt * SUB) it.c1 = nt * SUB;
     return it;
 }
 

@@ -7,9 +7,20 @@ namespace da {
 constexpr int kHeadDim = 128;    // only head_dim supported
 constexpr int kTile = 32;        // scheduling granule in tokens: splits begin and end on tiles of a block
 
-// One MicroAttention launch.  A work item is a (request, split, kv-head, head tile): the split's
-// tokens are read once and serve the head tile's q-heads.  The launch is persistent: workgroup b
-// handles items b, b + gridDim.x, ... (odd rounds mirrored) of the item list.
+// One split of one request (host-made, 32 bytes: one scalar load on the device).
+struct SplitEntry {
+    int32_t r;         // request
+    int32_t j;         // split index inside the request
+    int32_t t0, t1;    // tiles [t0, t1) of the request
+    int32_t ns;        // splits of the request
+    int32_t pad;
+    int64_t row_base;  // first partial row of the request
+};
+
+// One MicroAttention launch.  A work item is a (split, kv-head, head tile): the split's tokens are
+// read once and serve the head tile's q-heads.  The launch is persistent: workgroup b reads, for
+// (kv-head, head tile) number b % per_split, the splits entries[range_start[m] .. range_start[m+1])
+// with m = b / per_split, one after the other.
 struct MicroParams {
     const void *q;
     const void *k_pool;
@@ -21,18 +32,15 @@ struct MicroParams {
     float *part_e;
     float *out;  // used only for requests with one split when direct_out != 0
     float *lse;  // may be null
-    const int32_t *order;        // [B] request ids, processing order
-    const int32_t *item_prefix;  // [B+1] first work item of order[i]
-    const int32_t *nsplits;      // [B] by request id
-    const int64_t *row_base;     // [B] by request id: first partial row of the request
+    const SplitEntry *entries;   // every split of every request, in reading order
+    const int32_t *range_start;  // [ranges + 1]
     int32_t *err_flag;
     int32_t B, Hq, Hkv, G, T, max_blocks, num_phys;
     int32_t head_tile;          // q-heads served per work item
     int32_t head_tiles;         // ceil(G / head_tile)
     int32_t q_bf16;
     int32_t direct_out;
-    int32_t num_items;
-    int32_t fixed_split_tiles;  // > 0: split j = tiles [j*f, (j+1)*f); 0: split j = tiles [j*nt/ns, (j+1)*nt/ns)
+    int32_t per_split;          // Hkv * head_tiles
     int64_t stride_block, stride_head, stride_token;  // elements
     float scale_log2e;          // scale * log2(e): scores are kept in base-2 units inside the kernels
 };

@@ -115,8 +115,15 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
         }
     };
 
+    // this workgroup's run of splits and its (kv-head, head tile)
+    const int run = blockIdx.x / p.per_split;
+    const int combo = blockIdx.x - run * p.per_split;
+    const int kvh = combo / p.head_tiles;
+    const int ht = combo - kvh * p.head_tiles;
+    const int e_begin = table_load(p.range_start, run);
+    const int e_end = table_load(p.range_start, run + 1);
     int round = 0;
-    ItemInfo it = decode_item<kChunk>(p, item_of(blockIdx.x, 0, gridDim.x));
+    ItemInfo it = decode_item<kChunk>(p, e_begin, e_end, kvh, ht);
     Chunk cur = first_chunk<kChunk>(p, it, wave, lane);
     u32x4 kr[8], vr[8], qreg[4];
     load_k(fetch_of(cur), kr);
@@ -133,7 +140,7 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
         // before this item's result is merged
         const int buf = round & 1;
         ++round;
-        const ItemInfo nit = decode_item<kChunk>(p, item_of(blockIdx.x, round, gridDim.x));
+        const ItemInfo nit = decode_item<kChunk>(p, e_begin + round, e_end, kvh, ht);
         const Chunk ncur = first_chunk<kChunk>(p, nit, wave, lane);
 
         // every step issues 8 V loads and 8 K loads; kr always holds the K rows of `cur`
@@ -279,7 +286,6 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
 
 hipError_t launch_micro_attention_mfma(const MicroParams &p, int grid, hipStream_t stream)
 {
-    if (p.num_items <= 0) return hipSuccess;
     if (p.head_tile != kHeadTile || !p.q_bf16 || grid < 1) return hipErrorInvalidValue;
     hipLaunchKernelGGL(micro_attention_mfma_kernel, dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     return hipGetLastError();

@@ -145,8 +145,15 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
         }
     };
 
+    // this workgroup's run of splits and its (kv-head, head tile)
+    const int run = blockIdx.x / p.per_split;
+    const int combo = blockIdx.x - run * p.per_split;
+    const int kvh = combo / p.head_tiles;
+    const int ht = combo - kvh * p.head_tiles;
+    const int e_begin = table_load(p.range_start, run);
+    const int e_end = table_load(p.range_start, run + 1);
     int round = 0;
-    ItemInfo it = decode_item<CH>(p, item_of(blockIdx.x, 0, gridDim.x));
+    ItemInfo it = decode_item<CH>(p, e_begin, e_end, kvh, ht);
     Chunk cur = first_chunk<CH>(p, it, wave, lane);
     u32x4 kr[NL], vr[NL];
     float qf[GT][EPL];
@@ -167,7 +174,7 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
         // before this item's result is merged
         const int buf = round & 1;
         ++round;
-        const ItemInfo nit = decode_item<CH>(p, item_of(blockIdx.x, round, gridDim.x));
+        const ItemInfo nit = decode_item<CH>(p, e_begin + round, e_end, kvh, ht);
         const Chunk ncur = first_chunk<CH>(p, nit, wave, lane);
 
         // every step issues NL V loads and NL K loads; kr always holds the K rows of `cur`
@@ -309,7 +316,6 @@ hipError_t launch_one(const MicroParams &p, int grid, hipStream_t stream)
 // head_tile must be 1, 2, 4 or 8.
 hipError_t launch_micro_attention_valu(const MicroParams &p, bool kv_bf16, int grid, hipStream_t stream)
 {
-    if (p.num_items <= 0) return hipSuccess;
     if (grid < 1) return hipErrorInvalidValue;
     switch (p.head_tile) {
     case 1: return kv_bf16 ? launch_one<true, 1, 8>(p, grid, stream) : launch_one<false, 1, 8>(p, grid, stream);

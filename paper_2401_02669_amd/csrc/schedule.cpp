@@ -2,24 +2,23 @@
 //
 // Section 5.3, Eq. 5 prices attention by the total number of cached tokens, and Section 3 allows a
 // sequence to be partitioned at any length.  So the unit of balance is the token, not the request or
-// the block: every request is cut, on 32-token tile boundaries, into nsplits near-equal splits whose
-// size is the same across the whole batch; each (split, kv-head, head tile) is one work item.  The
-// MicroAttention launch is persistent: `grid` workgroups (two per compute unit) each take items
-// b, b + grid, ... of the size-sorted list, so when the item count is a multiple of the grid every
-// workgroup reads the same number of bytes and there is no tail.
+// the block.  The tiles (32 tokens) of all requests are laid end to end, longest request first, and
+// that stream is cut into `ranges` runs of equal cost; a cut that falls inside a request splits it
+// there.  Every kv-head (and head tile) is read by its own set of `ranges` persistent workgroups, one
+// per run, so all workgroups of the launch read the same number of bytes, each request is split no
+// more than the balance needs, and all heads of a request share the same split boundaries.
 #include "schedule.h"
 
 #include <algorithm>
 #include <cmath>
-#include <cstdlib>
 #include <numeric>
 
 namespace da {
 
 namespace {
 constexpr int kGroupsPerCu = 2;          // persistent MicroAttention workgroups per compute unit
-constexpr int kMaxItemsPerGroup = 8;     // more, smaller items only add partial rows
 constexpr double kPartialBudget = 0.01;  // partial write + read traffic allowed, relative to KV bytes
+constexpr int64_t kSplitCostTiles = 4;   // fixed cost of one split (look-up, merge, partial rows), in tiles
 }
 
 int64_t tiles_of(int64_t L, int32_t T)
@@ -35,17 +34,6 @@ int64_t tile_first_token(int64_t t, int32_t T)
 {
     const int64_t tpb = (T + kTileTokens - 1) / kTileTokens;
     return (t / tpb) * T + (t % tpb) * kTileTokens;
-}
-
-void split_tiles(int64_t nt, int32_t ns, int32_t fixed, int32_t j, int64_t *first, int64_t *last)
-{
-    if (fixed > 0) {
-        *first = std::min<int64_t>(nt, (int64_t)j * fixed);
-        *last = std::min<int64_t>(nt, (int64_t)(j + 1) * fixed);
-    } else {
-        *first = (int64_t)j * nt / ns;
-        *last = ((int64_t)j + 1) * nt / ns;
-    }
 }
 
 da_status validate_problem(const da_problem &p)
@@ -88,18 +76,17 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
     if (kernel == DA_KERNEL_AUTO) kernel = (G > 1 && mfma_ok) ? DA_KERNEL_MFMA : DA_KERNEL_VALU;
     if (kernel == DA_KERNEL_MFMA && !mfma_ok) return DA_ERR_UNSUPPORTED;
     s.kernel = kernel;
+    s.waves = 4;
     if (kernel == DA_KERNEL_MFMA) {
         s.head_tile = 16;
-        s.waves = 4;
     } else {
         s.head_tile = 1;
         while (s.head_tile < G && s.head_tile < 8) s.head_tile *= 2;
-        s.waves = 4;
     }
     s.head_tiles = (G + s.head_tile - 1) / s.head_tile;
-    const int64_t per_split = (int64_t)p.num_kv_heads * s.head_tiles;  // items per (request, split)
+    const int64_t P = (int64_t)p.num_kv_heads * s.head_tiles;  // workgroups that read the same splits
 
-    // tiles per request
+    // tiles per request; reading order = longest first
     s.ntiles.resize(B);
     int64_t total_tiles = 0;
     for (int r = 0; r < B; ++r) {
@@ -108,85 +95,102 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
         s.ntiles[r] = (int32_t)tiles_of(L, T);
         total_tiles += s.ntiles[r];
     }
+    std::vector<int32_t> order(B);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return s.ntiles[a] > s.ntiles[b]; });
 
+    // cut positions (tile index inside the request) per request, in reading order
+    std::vector<std::vector<int32_t>> cuts(B);
     const int64_t slots = (int64_t)num_cus * kGroupsPerCu;
-    s.nsplits.assign(B, 1);
-    s.fixed_split_tiles = 0;
+    int64_t ranges = std::max<int64_t>(1, slots / P);
+    std::vector<int64_t> range_first_tile;  // auto mode: stream position where each range begins
     if (tuning.blocks_per_split > 0) {
         // caller's choice: every split is exactly this many blocks (1 = one partial per block)
-        const int64_t fixed = std::min<int64_t>((int64_t)tuning.blocks_per_split * tpb, INT32_MAX);
-        s.fixed_split_tiles = (int32_t)fixed;
-        for (int r = 0; r < B; ++r) s.nsplits[r] = (int32_t)std::max<int64_t>(1, (s.ntiles[r] + fixed - 1) / fixed);
+        const int64_t f = std::min<int64_t>((int64_t)tuning.blocks_per_split * tpb, INT32_MAX);
+        for (int r = 0; r < B; ++r)
+            for (int64_t t = f; t < s.ntiles[r]; t += f) cuts[r].push_back((int32_t)t);
     } else {
-        // item size (tiles), the same for the whole batch: at least one tile per wavefront and enough
-        // tokens that the item's partial rows (written once, read once) stay inside their budget;
-        // beyond that, at most kMaxItemsPerGroup items per persistent workgroup.
+        // a run must be worth its partial rows (written once, read once) and give every wavefront a tile
         const double esize = p.kv_dtype == DA_BF16 ? 2.0 : 4.0;
         const int heads_per_item = std::min(G, s.head_tile);
         const double partial_bytes = 2.0 * heads_per_item * (p.head_dim + 2) * 4.0;
         const double tile_bytes = 2.0 * p.head_dim * esize * kTileTokens;
         const int64_t t_min = std::max<int64_t>(s.waves, (int64_t)std::ceil(partial_bytes / (kPartialBudget * tile_bytes)));
-        const int64_t units = total_tiles * per_split;  // (tile, kv-head, head tile) units of work
-        const int64_t kmax = getenv("DA_EXP_KMAX") ? atoi(getenv("DA_EXP_KMAX")) : kMaxItemsPerGroup;  // EXPERIMENT
-        const int64_t k = std::max<int64_t>(1, std::min<int64_t>(kmax, units / (slots * t_min)));
-        double t_star = std::max<double>((double)units / (double)(k * slots), (double)s.waves);
-        if (units >= slots * t_min) t_star = std::max<double>(t_star, (double)t_min);
-        int64_t sum_ns = 0;
-        for (int r = 0; r < B; ++r) {
-            const int64_t n = std::max<int64_t>(1, std::min<int64_t>(std::max<int64_t>(1, s.ntiles[r]), (int64_t)std::llround(s.ntiles[r] / t_star)));
-            s.nsplits[r] = (int32_t)n;
-            sum_ns += n;
-        }
-        // make the item count a multiple of the grid when the batch is big enough: adjust the split
-        // counts of the requests that change their item size least
-        const int64_t q = slots / std::gcd(slots, per_split);
-        if (sum_ns * per_split > slots && B <= 1024 && q > 1) {
-            const int64_t rem = sum_ns % q;
-            int64_t delta = rem == 0 ? 0 : (rem * 2 <= q ? -rem : q - rem);  // splits to add (+) or drop (-)
-            for (int guard = 0; delta != 0 && guard < 4096; ++guard) {
-                int best = -1;
-                double best_cost = 0.0;
-                for (int r = 0; r < B; ++r) {
-                    const int64_t n = s.nsplits[r], nn = n + (delta > 0 ? 1 : -1);
-                    if (nn < 1 || nn > s.ntiles[r] || s.ntiles[r] / nn < s.waves) continue;
-                    // relative change of this request's item size
-                    const double cost = std::fabs((double)n / (double)nn - 1.0);
-                    if (best < 0 || cost < best_cost) { best = r; best_cost = cost; }
-                }
-                if (best < 0) break;
-                s.nsplits[best] += delta > 0 ? 1 : -1;
-                delta += delta > 0 ? -1 : 1;
+        ranges = std::max<int64_t>(1, std::min<int64_t>(ranges, total_tiles / t_min));
+        // equal-cost cut of the stream; a request costs its tiles plus a fixed amount per split
+        const double total_cost = (double)total_tiles + (double)kSplitCostTiles * B;
+        int64_t m = 1;          // next boundary to place
+        double cost_before = 0; // cost of the requests before the current one
+        for (int i = 0; i < B && m < ranges; ++i) {
+            const int r = order[i];
+            const double cost_end = cost_before + kSplitCostTiles + s.ntiles[r];
+            while (m < ranges) {
+                const double x = total_cost * (double)m / (double)ranges;
+                if (x >= cost_end) break;
+                int64_t t = (int64_t)std::llround(x - cost_before - kSplitCostTiles);
+                t = std::max<int64_t>(0, std::min<int64_t>(t, s.ntiles[r]));
+                const int64_t prev = cuts[r].empty() ? 0 : cuts[r].back();
+                // keep splits at least one tile per wavefront long; a boundary that would fall too close
+                // to the previous one or to an end of the request moves to that end (no split there)
+                if (t - prev >= s.waves && s.ntiles[r] - t >= s.waves) cuts[r].push_back((int32_t)t);
+                ++m;
             }
+            cost_before = cost_end;
         }
     }
 
+    // splits, partial rows, entries in reading order
+    s.nsplits.assign(B, 1);
     s.row_base.assign(B, 0);
+    s.first_entry.assign(B, 0);
     s.max_nsplits = 1;
     int64_t rows = 0;
     for (int r = 0; r < B; ++r) {
-        s.max_nsplits = std::max<int32_t>(s.max_nsplits, s.nsplits[r]);
+        s.nsplits[r] = (int32_t)cuts[r].size() + 1;
+        s.max_nsplits = std::max(s.max_nsplits, s.nsplits[r]);
         s.row_base[r] = rows;
         rows += (int64_t)s.nsplits[r] * p.num_q_heads;
     }
     s.num_partials = rows;
-
-    // items in order of decreasing size, so that each round of the persistent grid holds like-sized items
-    std::vector<double> item_tiles(B);
-    for (int r = 0; r < B; ++r) item_tiles[r] = (double)s.ntiles[r] / s.nsplits[r];
-    s.order.resize(B);
-    std::iota(s.order.begin(), s.order.end(), 0);
-    std::stable_sort(s.order.begin(), s.order.end(), [&](int a, int b) { return item_tiles[a] > item_tiles[b]; });
-    s.item_prefix.assign(B + 1, 0);
-    int64_t items = 0;
+    s.entries.clear();
     for (int i = 0; i < B; ++i) {
-        s.item_prefix[i] = (int32_t)items;
-        items += (int64_t)s.nsplits[s.order[i]] * per_split;
-        if (items > INT32_MAX / 2) return DA_ERR_UNSUPPORTED;
+        const int r = order[i];
+        s.first_entry[r] = (int32_t)s.entries.size();
+        for (int j = 0; j < s.nsplits[r]; ++j) {
+            SplitEntry e;
+            e.r = r;
+            e.j = j;
+            e.t0 = j == 0 ? 0 : cuts[r][j - 1];
+            e.t1 = j + 1 == s.nsplits[r] ? s.ntiles[r] : cuts[r][j];
+            e.ns = s.nsplits[r];
+            e.pad = 0;
+            e.row_base = s.row_base[r];
+            s.entries.push_back(e);
+        }
     }
-    s.item_prefix[B] = (int32_t)items;
-    s.num_items = items;
-    const int64_t gmult = getenv("DA_EXP_GRIDMULT") ? atoi(getenv("DA_EXP_GRIDMULT")) : 1;  // EXPERIMENT
-    s.grid = (int32_t)std::max<int64_t>(1, std::min<int64_t>(items, slots * gmult));
+    if ((int64_t)s.entries.size() * P > INT32_MAX / 2) return DA_ERR_UNSUPPORTED;
+    s.num_items = (int64_t)s.entries.size() * P;
+
+    // runs of consecutive entries of equal cost (in auto mode this reproduces the cuts made above)
+    const int64_t E = (int64_t)s.entries.size();
+    ranges = std::max<int64_t>(1, std::min<int64_t>(ranges, E));
+    double total_cost = 0;
+    for (const SplitEntry &e : s.entries) total_cost += kSplitCostTiles + (e.t1 - e.t0);
+    s.range_start.assign(1, 0);
+    double acc = 0;
+    for (int64_t i = 0; i < E; ++i) {
+        const double c = kSplitCostTiles + (s.entries[i].t1 - s.entries[i].t0);
+        const int64_t m = (int64_t)s.range_start.size();  // boundary being looked for
+        // start a new run before entry i when the boundary lies nearer to its start than to its end,
+        // while leaving at least one entry for every run still to come
+        if (m < ranges && i > s.range_start.back() &&
+            (acc + 0.5 * c >= total_cost * (double)m / (double)ranges || E - i <= ranges - m))
+            s.range_start.push_back((int32_t)i);
+        acc += c;
+    }
+    s.ranges = (int32_t)s.range_start.size();
+    s.range_start.push_back((int32_t)E);
+    s.grid = (int32_t)(s.ranges * P);
     return DA_OK;
 }
 

@@ -56,7 +56,7 @@ def lib():
         vp, i32p, i64p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
         L.da_status_string.restype = ctypes.c_char_p
         L.da_status_string.argtypes = [ctypes.c_int]
-        L.da_plan_schedule.argtypes = [ctypes.POINTER(DaProblem), vp, ctypes.POINTER(DaTuning), vp, vp, i64p, i64p, i32p]
+        L.da_plan_schedule.argtypes = [ctypes.POINTER(DaProblem), vp, ctypes.POINTER(DaTuning), vp, i64p, i64p, i32p, i32p, i64p]
         L.da_plan_create.argtypes = [ctypes.POINTER(DaProblem), vp, ctypes.POINTER(DaTuning), vp, ctypes.POINTER(vp)]
         L.da_plan_update.argtypes = [vp, vp, vp]
         L.da_plan_destroy.argtypes = [vp]
@@ -112,18 +112,20 @@ def _host_i32(seq_lens_host):
 
 
 def plan_schedule(problem, seq_lens_host, blocks_per_split=0, num_cus=0, kernel=DA_KERNEL_AUTO):
-    """Host-only schedule (no GPU needed): dict(nsplits, order, num_items, num_partials, kernel)."""
+    """Host-only schedule (no GPU needed): dict(nsplits, num_items, num_partials, kernel, workgroups,
+    max_workgroup_tokens)."""
     B = problem.batch
     lens = _host_i32(seq_lens_host)
-    ns, order = (ctypes.c_int32 * B)(), (ctypes.c_int32 * B)()
-    items, parts, kern = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32()
+    ns = (ctypes.c_int32 * B)()
+    items, parts, kern, wgs = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32(), ctypes.c_int32()
+    worst = ctypes.c_int64()
     tuning = DaTuning(blocks_per_split, num_cus, kernel)
     st = lib().da_plan_schedule(ctypes.byref(problem), ctypes.cast(lens, ctypes.c_void_p), ctypes.byref(tuning),
-                                ctypes.cast(ns, ctypes.c_void_p), ctypes.cast(order, ctypes.c_void_p),
-                                ctypes.byref(items), ctypes.byref(parts), ctypes.byref(kern))
+                                ctypes.cast(ns, ctypes.c_void_p), ctypes.byref(items), ctypes.byref(parts),
+                                ctypes.byref(kern), ctypes.byref(wgs), ctypes.byref(worst))
     _check(st, "da_plan_schedule")
-    return dict(nsplits=list(ns), order=list(order), num_items=items.value, num_partials=parts.value,
-                kernel=kern.value)
+    return dict(nsplits=list(ns), num_items=items.value, num_partials=parts.value, kernel=kern.value,
+                workgroups=wgs.value, max_workgroup_tokens=worst.value)
 
 
 def _stream_ptr(stream=None):

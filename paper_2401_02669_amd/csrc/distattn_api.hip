@@ -21,18 +21,19 @@ constexpr int kRing = 4;  // pinned staging slots for table uploads
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Device tables of a plan: [entries | range_start | nsplits | row_base | error flag], sized for a capacity.
+// Device tables of a plan: [error flag | range_start | nsplits | row_base | entries], sized for a capacity.
+// Everything behind the error flag is uploaded in one copy that ends with the last used entry.
 struct TableLayout {
-    size_t entries, range_start, nsplits, row_base, err, total;
+    size_t err, range_start, nsplits, row_base, entries, total;
     TableLayout(size_t cap_entries, size_t cap_ranges, size_t batch)
     {
         size_t off = 0;
-        entries = off;     off = align_up(off + sizeof(da::SplitEntry) * cap_entries, 32);
+        err = off;         off = align_up(off + sizeof(int32_t), 32);
         range_start = off; off = align_up(off + sizeof(int32_t) * (cap_ranges + 1), 32);
         nsplits = off;     off = align_up(off + sizeof(int32_t) * batch, 32);
         row_base = off;    off = align_up(off + sizeof(int64_t) * batch, 32);
-        total = off;  // uploaded part
-        err = off;    off = align_up(off + sizeof(int32_t), 32);
+        entries = off;     off = align_up(off + sizeof(da::SplitEntry) * cap_entries, 32);
+        total = off;
     }
 };
 
@@ -78,7 +79,7 @@ da_status reserve_tables(da_plan *pl, hipStream_t stream)
     pl->cap_entries = need_e * 2 + 1024;
     pl->cap_ranges = std::max<size_t>(need_r * 2, 1024);
     const TableLayout lay = layout_of(pl);
-    bool ok = hipMalloc((void **)&pl->dev, lay.err + 32) == hipSuccess;
+    bool ok = hipMalloc((void **)&pl->dev, lay.total) == hipSuccess;
     for (int i = 0; ok && i < kRing; ++i) ok = hipHostMalloc((void **)&pl->stage[i], lay.total, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipMemsetAsync(pl->dev + lay.err, 0, 32, stream) == hipSuccess;
     return ok ? DA_OK : DA_ERR_HIP;
@@ -102,10 +103,8 @@ da_status upload(da_plan *pl, hipStream_t stream)
     std::memcpy(h + lay.range_start, s.range_start.data(), sizeof(int32_t) * s.range_start.size());
     std::memcpy(h + lay.nsplits, s.nsplits.data(), sizeof(int32_t) * B);
     std::memcpy(h + lay.row_base, s.row_base.data(), sizeof(int64_t) * B);
-    // two copies: the used part of the entry table, and the three small tables behind it
-    const size_t used_entries = sizeof(da::SplitEntry) * s.entries.size();
-    if (hipMemcpyAsync(pl->dev + lay.entries, h + lay.entries, used_entries, hipMemcpyHostToDevice, stream) != hipSuccess ||
-        hipMemcpyAsync(pl->dev + lay.range_start, h + lay.range_start, lay.total - lay.range_start, hipMemcpyHostToDevice,
+    const size_t end = lay.entries + sizeof(da::SplitEntry) * s.entries.size();
+    if (hipMemcpyAsync(pl->dev + lay.range_start, h + lay.range_start, end - lay.range_start, hipMemcpyHostToDevice,
                        stream) != hipSuccess)
         return DA_ERR_HIP;
     if (hipEventRecord(pl->ev[slot], stream) != hipSuccess) return DA_ERR_HIP;

@@ -129,3 +129,18 @@ def test_explicit_blocks_per_split_is_honoured():
     assert s["nsplits"] == [15, 1, 1]
     s = da.plan_schedule(p, lens, blocks_per_split=1000)
     assert s["nsplits"] == [1, 1, 1]
+
+
+def test_schedule_of_a_large_batch_is_cheap_and_balanced():
+    import time
+    rng = np.random.RandomState(0)
+    lens = np.floor(np.exp(rng.uniform(np.log(16), np.log(200000), size=4096))).astype(np.int64)
+    p = problem(B=4096, Hq=32, Hkv=8, T=256, max_blocks=int((lens.max() + 255) // 256), num_phys=1 << 20)
+    t0 = time.perf_counter()
+    for _ in range(5):
+        s = da.plan_schedule(p, lens, num_cus=256)
+    dt = (time.perf_counter() - t0) / 5
+    assert dt < 0.02, dt   # a few hundred microseconds in practice
+    assert s["workgroups"] == 512
+    assert s["max_workgroup_tokens"] <= 1.03 * float(lens.sum()) / 64 + 64
+    assert sum(s["nsplits"]) <= 4096 + 63

@@ -183,6 +183,49 @@ def test_deterministic_and_plan_update():
     plan.close()
 
 
+def test_many_small_requests_share_workgroups():
+    # hundreds of short requests: most workgroups walk several requests, a few requests are cut
+    rng = np.random.RandomState(3)
+    lens = [int(x) for x in rng.randint(0, 300, size=600)] + [5000, 7777]
+    w = synth.make(custom(lens, Hq=8, Hkv=8, T=32), DEV)
+    ref_out, ref_lse = oracle_attention(w)
+    for kernel in (da.DA_KERNEL_VALU, da.DA_KERNEL_MFMA):
+        out, lse, flags = gpu_attention(w, kernel=kernel)
+        assert flags == 0
+        assert_parity(out, lse, ref_out, ref_lse, "bf16", "many small, kernel=%d" % kernel)
+        for r in (0, 17, 599, 600, 601):
+            _, rel = errors(out[r], ref_out[r])
+            assert rel <= TOL["bf16"]["rel_l2"]
+
+
+def test_more_head_groups_than_workgroup_slots():
+    # Hkv * head tiles = 1024 > 512 persistent slots: one run per (kv-head, head tile), requests never split
+    w = synth.make(custom([100, 37], Hq=128 * 64, Hkv=128, T=16), DEV)
+    prob = da.make_problem(w["q"], w["k_pool"], w["block_table"], w["scale"])
+    s = da.plan_schedule(prob, w["seq_lens_host"].tolist(), kernel=da.DA_KERNEL_VALU)
+    assert s["workgroups"] == 1024 and s["nsplits"] == [1, 1]
+    ref_out, ref_lse = oracle_attention(w)
+    for kernel in (da.DA_KERNEL_VALU, da.DA_KERNEL_AUTO):
+        out, lse, flags = gpu_attention(w, kernel=kernel)
+        assert_parity(out, lse, ref_out, ref_lse, "bf16", "many heads kernel=%d" % kernel)
+
+
+def test_plan_update_grows_its_tables():
+    T = 16
+    w = synth.make(custom([6400, 6400, 6400, 6400], Hq=2, Hkv=2, T=T), DEV)
+    short = [16, 16, 16, 16]
+    prob = da.make_problem(w["q"], w["k_pool"], w["block_table"], w["scale"])
+    plan = da.Plan(prob, short, blocks_per_split=1)     # 4 splits in all
+    assert plan.num_partials == 4 * 2
+    plan.update(w["seq_lens_host"].tolist())            # 1600 splits: more than the tables were made for
+    assert plan.num_partials == 1600 * 2
+    out, lse = plan.attention(w["q"], w["k_pool"], w["v_pool"], w["block_table"], w["seq_lens"])
+    torch.cuda.synchronize()
+    ref_out, ref_lse = oracle_attention(w)
+    assert_parity(out.cpu().numpy(), lse.cpu().numpy(), ref_out, ref_lse, "bf16", "grown plan")
+    plan.close()
+
+
 def test_bad_block_ids_are_skipped_and_flagged():
     w = synth.make(custom([640, 640], Hq=2, Hkv=2, T=64, spare_frac=0.0), DEV)
     table = w["block_table"].clone()

@@ -121,9 +121,12 @@ typedef struct da_plan da_plan; /* opaque: split schedule of one batch + its sma
  * da_plan_update: re-plan the same problem for new lengths in place.  Ordered
  *   on `stream` after earlier launches that used the plan; allocates (and
  *   waits for `stream`) only if the split table outgrew its capacity.
- * The lengths given here must equal the device seq_lens passed to the launch
- * calls: the host values decide how the work is cut, the device values where
- * each request's valid tokens end.
+ * The lengths given here decide only how the work is cut; which tokens are
+ * read follows the device seq_lens passed to the launch calls (the last split
+ * of a request runs to that request's device length, every other split stops
+ * there at the latest).  A plan made for slightly different lengths, as in a
+ * decode loop that re-plans every few steps, therefore still gives exact
+ * results, only a less even balance; da_plan_split reports the planned cut.
  * A plan serves one launch at a time per stream order; it is not to be used
  * from two host threads at once.
  * Errors: DA_ERR_INVALID_ARG / DA_ERR_UNSUPPORTED from validation (before any

@@ -76,22 +76,23 @@ __device__ __forceinline__ ItemInfo decode_item(const MicroParams &p, int e, int
     it.j = ent->j;
     it.ns = ent->ns;
     it.row_base = ent->row_base;
-    it.c0 = ent->t0 * SUB;
-    it.c1 = ent->t1 * SUB;
     int L = table_load(p.seq_lens, it.r);
     L = L < 0 ? 0 : L;
     const int64_t cap = (int64_t)p.max_blocks * p.T;
     if ((int64_t)L > cap) L = (int)cap;
     it.L = L;
-    // never walk past the tiles the device length really has (the split table was made from host lengths)
+    // The device length decides where the request ends: the split table was cut from host lengths
+    // that may be stale, and its last split of a request is open-ended.
     const int tpb = (p.T + kTile - 1) / kTile;
     int nt = 0;
     if (L > 0) {
         const int nb = (L + p.T - 1) / p.T;
         nt = (nb - 1) * tpb + (L - (nb - 1) * p.T + kTile - 1) / kTile;
     }
-    if (it.c0 > nt * SUB) it.c0 = nt * SUB;
-    if (it.c1 > nt * SUB) it.c1 = nt * SUB;
+    const int t0 = ent->t0 < nt ? ent->t0 : nt;
+    const int t1 = (it.j + 1 == it.ns || ent->t1 > nt) ? nt : ent->t1;
+    it.c0 = t0 * SUB;
+    it.c1 = t1 * SUB;
     return it;
 }
 

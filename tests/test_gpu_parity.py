@@ -226,6 +226,27 @@ def test_plan_update_grows_its_tables():
     plan.close()
 
 
+def test_stale_plan_still_gives_exact_results():
+    # the plan was cut for other lengths than the device holds: longer, shorter, zero, from zero
+    T = 64
+    planned = [5000, 3000, 0, 700, 64]
+    actual = [5100, 1500, 90, 0, 6400]
+    w = synth.make(custom(actual, Hq=8, Hkv=2, T=T), DEV)
+    ref_out, ref_lse = oracle_attention(w)
+    prob = da.make_problem(w["q"], w["k_pool"], w["block_table"], w["scale"])
+    for kernel in (da.DA_KERNEL_VALU, da.DA_KERNEL_MFMA):
+        for bps in (0, 2):
+            plan = da.Plan(prob, planned, blocks_per_split=bps, kernel=kernel)
+            out, lse = plan.attention(w["q"], w["k_pool"], w["v_pool"], w["block_table"], w["seq_lens"])
+            po, pm, pe = plan.partial(w["q"], w["k_pool"], w["v_pool"], w["block_table"], w["seq_lens"])
+            out2, lse2 = plan.combine(po, pm, pe)
+            torch.cuda.synchronize()
+            assert plan.error_flags() == 0
+            plan.close()
+            assert_parity(out.cpu().numpy(), lse.cpu().numpy(), ref_out, ref_lse, "bf16", "stale plan fused")
+            assert_parity(out2.cpu().numpy(), lse2.cpu().numpy(), ref_out, ref_lse, "bf16", "stale plan two-step")
+
+
 def test_bad_block_ids_are_skipped_and_flagged():
     w = synth.make(custom([640, 640], Hq=2, Hkv=2, T=64, spare_frac=0.0), DEV)
     table = w["block_table"].clone()

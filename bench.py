@@ -169,8 +169,8 @@ def main():
         "metric": "kv_read_hbm_GBps", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if w["dtype"] == "f32" else "bf16 K/V, f32 accumulate", "data": "synthetic",
-        "config": {"workload": w["name"], "batch": w["B"], "q_heads": w["Hq"], "kv_heads": w["Hkv"], "head_dim": 128,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w["name"], "kv_storage": w["dtype"], "batch": w["B"], "q_heads": w["Hq"], "kv_heads": w["Hkv"], "head_dim": 128,
                    "block_tokens": w["T"], "tokens_total": int(w["seq_lens_host"].sum()),
                    "max_len": int(w["seq_lens_host"].max()), "kv_bytes": int(kv_bytes),
                    "work_items": sched["num_items"], "workgroups": sched["workgroups"], "partials": sched["num_partials"],

@@ -62,7 +62,8 @@ typedef enum {
     DA_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, Hq % Hkv != 0, misaligned stride ... */
     DA_ERR_UNSUPPORTED = 2, /* head_dim != 128, block_tokens % 16 != 0, unknown dtype, group > 64 */
     DA_ERR_WORKSPACE = 3,   /* workspace smaller than da_workspace_bytes() */
-    DA_ERR_HIP = 4          /* a HIP runtime call failed (no device, launch failure, out of memory) */
+    DA_ERR_HIP = 4,         /* a HIP runtime call failed (no device, launch failure, out of memory) */
+    DA_ERR_NO_SPACE = 5     /* the block pool has too few free blocks */
 } da_status;
 
 typedef enum { DA_F32 = 0, DA_BF16 = 1 } da_dtype;
@@ -188,6 +189,44 @@ da_status da_combine(const da_plan *plan, const float *part_o, const float *part
 da_status da_attention(const da_plan *plan, const void *q, const void *k_pool, const void *v_pool,
                        const int32_t *block_table, const int32_t *seq_lens, float *out, float *lse,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * KV append, the step before attention in every decode iteration (Section 4:
+ * the cache is sliced along the sequence dimension so that newly generated
+ * tokens join the sub-block layout as they are produced).  k_new / v_new hold
+ * one new token per request, [batch][num_kv_heads][head_dim] in kv_dtype
+ * (16-byte aligned).  For every request r with L = seq_lens[r] >= 0 the rows
+ * are written to slot L % block_tokens of block block_table[r][L / block_tokens]
+ * of both pools, for all kv-heads, and seq_lens[r] becomes L + 1 (device side,
+ * in stream order: an attention launch that follows on the same stream sees
+ * the new token).  L < 0 marks an inactive batch slot and is left alone.  The
+ * block must already be in the table (da_block_pool_grow); a request whose
+ * position has no valid block (bit 0) or whose table row is full (bit 1) is
+ * skipped and the bit is OR-ed into *err_flags (device int32, may be NULL).
+ * Uses of `problem`: batch, num_kv_heads, head_dim, block_tokens,
+ * max_blocks_per_seq, num_phys_blocks, kv_dtype and the three strides.
+ */
+da_status da_append(const da_problem *problem, const void *k_new, const void *v_new, void *k_pool, void *v_pool,
+                    const int32_t *block_table, int32_t *seq_lens, int32_t *err_flags, void *stream);
+
+/*
+ * Host-side free list of physical KV blocks (Section 4: sub-blocks are the
+ * unit in which the growing cache is managed; Section 5.1: they are pooled).
+ * No GPU call.  da_block_pool_grow appends fresh block ids to a request's HOST
+ * block-table row so that it can hold new_len tokens (it held cur_len); the
+ * caller copies the changed entries to the device table.  If the pool has too
+ * few free blocks nothing is taken and DA_ERR_NO_SPACE is returned.
+ * da_block_pool_release returns the ceil(len / block_tokens) blocks of a row
+ * and sets the entries to -1; an id that the pool did not hand out, or a
+ * duplicate, is DA_ERR_INVALID_ARG and nothing is returned.
+ */
+typedef struct da_block_pool da_block_pool;
+da_status da_block_pool_create(int32_t num_phys_blocks, da_block_pool **pool);
+da_status da_block_pool_destroy(da_block_pool *pool);
+da_status da_block_pool_free_count(const da_block_pool *pool, int32_t *count);
+da_status da_block_pool_grow(da_block_pool *pool, int32_t block_tokens, int32_t max_blocks_per_seq,
+                             int32_t *block_table_row_host, int32_t cur_len, int32_t new_len);
+da_status da_block_pool_release(da_block_pool *pool, int32_t block_tokens, int32_t *block_table_row_host, int32_t len);
 
 /*
  * Measurement aid, not part of the attention path: streams `bytes` of device memory once with

@@ -11,6 +11,7 @@ raw bit patterns.  Pools are addressed as
   attention()        Section 4, Eq. 1 (plain definition, two passes)
   micro_attention()  Section 4, m_j / e_j equation and Eq. 2
   aggregate()        Section 4, m_g / e_g equation and Eq. 3
+  append()           Section 4: a new token's K/V rows join the block layout
 """
 import ctypes
 import os
@@ -64,6 +65,8 @@ def _load():
         _lib.oracle_aggregate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                           ctypes.c_void_p, ctypes.c_void_p]
+        _lib.oracle_append.restype = ctypes.c_int
+        _lib.oracle_append.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int] * 7 + [ctypes.c_int64] * 3
     return _lib
 
 
@@ -162,3 +165,23 @@ def aggregate(MA, m, e, nparts, num_q_heads):
     if rc != 0:
         raise ValueError("oracle_aggregate rejected its arguments")
     return out, lse
+
+
+def append(k_new, v_new, k_pool, v_pool, block_table, seq_lens):
+    """KV append in place: writes the new rows into the (contiguous, writable) numpy pools and bumps seq_lens.
+
+    k_new / v_new: [B][Hkv][d]; pools [P][Hkv][T][d]; block_table int32 [B][max_blocks]; seq_lens int32 [B]."""
+    B, Hkv, d = k_new.shape
+    P, Hkv2, T, d2 = k_pool.shape
+    assert (Hkv2, d2) == (Hkv, d) and v_pool.shape == k_pool.shape and v_new.shape == k_new.shape
+    assert k_pool.dtype == k_new.dtype == v_pool.dtype == v_new.dtype and _dtype_code(k_pool) in (F32, BF16)
+    for a in (k_pool, v_pool, seq_lens):
+        assert a.flags["C_CONTIGUOUS"] and a.flags["WRITEABLE"]
+    assert block_table.dtype == np.int32 and seq_lens.dtype == np.int32 and block_table.flags["C_CONTIGUOUS"]
+    k_new = np.ascontiguousarray(k_new)
+    v_new = np.ascontiguousarray(v_new)
+    rc = _load().oracle_append(k_new.ctypes.data, v_new.ctypes.data, k_pool.ctypes.data, v_pool.ctypes.data,
+                               block_table.ctypes.data, seq_lens.ctypes.data, B, Hkv, d, T, block_table.shape[1], P,
+                               k_pool.itemsize, Hkv * T * d, T * d, d)
+    if rc != 0:
+        raise ValueError("oracle_append rejected its arguments")

@@ -241,3 +241,40 @@ int oracle_aggregate(int B, int Hq, int d, const int32_t *nparts,
     }
     return 0;
 }
+
+/*
+ * KV append, written out as its definition (Section 4: new tokens join the
+ * sub-block layout along the sequence dimension).  For every request r with
+ * L = seq_lens[r] >= 0: the K and V rows of the new token (k_new / v_new,
+ * [B][Hkv][d] in the stored dtype, raw bytes) go to slot L % T of physical
+ * block block_table[r][L / T] of both pools, for every kv-head, and
+ * seq_lens[r] becomes L + 1.  A request whose position has no valid block, or
+ * whose table row is full, is left untouched.  elem_size is 2 (bf16) or 4.
+ */
+int oracle_append(const void *k_new, const void *v_new, void *k_pool, void *v_pool,
+                  const int32_t *block_table, int32_t *seq_lens,
+                  int B, int Hkv, int d, int T, int max_blocks, int num_phys, int elem_size,
+                  int64_t stride_block, int64_t stride_head, int64_t stride_token)
+{
+    if (!k_new || !v_new || !k_pool || !v_pool || !block_table || !seq_lens)
+        return 1;
+    for (int r = 0; r < B; ++r) {
+        int64_t L = seq_lens[r];
+        if (L < 0)
+            continue;
+        int64_t logical_block = L / T, slot = L % T;
+        if (logical_block >= max_blocks)
+            continue;
+        int64_t pb = block_table[(int64_t)r * max_blocks + logical_block];
+        if (pb < 0 || pb >= num_phys)
+            continue;
+        for (int g = 0; g < Hkv; ++g) {
+            int64_t dst = (pb * stride_block + g * stride_head + slot * stride_token) * elem_size;
+            int64_t src = (((int64_t)r * Hkv + g) * d) * elem_size;
+            memcpy((char *)k_pool + dst, (const char *)k_new + src, (size_t)d * elem_size);
+            memcpy((char *)v_pool + dst, (const char *)v_new + src, (size_t)d * elem_size);
+        }
+        seq_lens[r] = (int32_t)(L + 1);
+    }
+    return 0;
+}

@@ -170,6 +170,7 @@ const char *da_status_string(da_status s)
     case DA_ERR_UNSUPPORTED: return "unsupported configuration";
     case DA_ERR_WORKSPACE: return "workspace too small or misaligned";
     case DA_ERR_HIP: return "HIP runtime error";
+    case DA_ERR_NO_SPACE: return "block pool exhausted";
     }
     return "unknown status";
 }

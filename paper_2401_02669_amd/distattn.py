@@ -12,14 +12,16 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdistattn.so")
 
-DA_OK, DA_ERR_INVALID_ARG, DA_ERR_UNSUPPORTED, DA_ERR_WORKSPACE, DA_ERR_HIP = range(5)
+DA_OK, DA_ERR_INVALID_ARG, DA_ERR_UNSUPPORTED, DA_ERR_WORKSPACE, DA_ERR_HIP, DA_ERR_NO_SPACE = range(6)
 DA_F32, DA_BF16 = 0, 1
 DA_KERNEL_AUTO, DA_KERNEL_VALU, DA_KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = [
     "da_status_string", "da_plan_schedule", "da_plan_create", "da_plan_update", "da_plan_destroy",
     "da_plan_num_partials", "da_plan_split", "da_plan_nsplits", "da_workspace_bytes", "da_plan_error",
-    "da_partial", "da_combine", "da_attention", "da_probe_read",
+    "da_partial", "da_combine", "da_attention", "da_probe_read", "da_append",
+    "da_block_pool_create", "da_block_pool_destroy", "da_block_pool_free_count", "da_block_pool_grow",
+    "da_block_pool_release",
 ]
 
 
@@ -69,6 +71,12 @@ def lib():
         L.da_combine.argtypes = [vp] * 7
         L.da_attention.argtypes = [vp] * 9 + [ctypes.c_size_t, vp]
         L.da_probe_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, vp, vp]
+        L.da_append.argtypes = [ctypes.POINTER(DaProblem)] + [vp] * 8
+        L.da_block_pool_create.argtypes = [ctypes.c_int32, ctypes.POINTER(vp)]
+        L.da_block_pool_destroy.argtypes = [vp]
+        L.da_block_pool_free_count.argtypes = [vp, i32p]
+        L.da_block_pool_grow.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp, ctypes.c_int32, ctypes.c_int32]
+        L.da_block_pool_release.argtypes = [vp, ctypes.c_int32, vp, ctypes.c_int32]
         for name in EXPORTS[1:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -236,3 +244,45 @@ def probe_read(src, segment_bytes, workgroups, variant, sink, stream=None):
     st = lib().da_probe_read(_ptr(src), src.numel() * src.element_size(), segment_bytes, workgroups, variant,
                              _ptr(sink), _stream_ptr(stream))
     _check(st, "da_probe_read")
+
+
+def append(problem, k_new, v_new, k_pool, v_pool, block_table, seq_lens, err_flags=None, stream=None):
+    """Enqueue da_append: one new token per request joins the pools; seq_lens is incremented on the device."""
+    st = lib().da_append(ctypes.byref(problem), _ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                         _ptr(seq_lens), _ptr(err_flags), _stream_ptr(stream))
+    _check(st, "da_append")
+
+
+class BlockPool:
+    """Host free list of physical KV blocks (da_block_pool).  Rows are numpy int32 views of the host block table."""
+
+    def __init__(self, num_phys_blocks):
+        self._h = ctypes.c_void_p()
+        _check(lib().da_block_pool_create(num_phys_blocks, ctypes.byref(self._h)), "da_block_pool_create")
+
+    def close(self):
+        if self._h:
+            lib().da_block_pool_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def free_count(self):
+        n = ctypes.c_int32()
+        _check(lib().da_block_pool_free_count(self._h, ctypes.byref(n)), "da_block_pool_free_count")
+        return n.value
+
+    def grow(self, row, block_tokens, cur_len, new_len):
+        assert row.dtype.itemsize == 4 and row.flags["C_CONTIGUOUS"]
+        st = lib().da_block_pool_grow(self._h, block_tokens, row.shape[0], ctypes.c_void_p(row.ctypes.data), cur_len, new_len)
+        _check(st, "da_block_pool_grow")
+
+    def release(self, row, block_tokens, length):
+        assert row.dtype.itemsize == 4 and row.flags["C_CONTIGUOUS"]
+        st = lib().da_block_pool_release(self._h, block_tokens, ctypes.c_void_p(row.ctypes.data), length)
+        _check(st, "da_block_pool_release")

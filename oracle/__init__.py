@@ -45,6 +45,7 @@ class _Problem(ctypes.Structure):
         ("stride_block", ctypes.c_int64), ("stride_head", ctypes.c_int64),
         ("stride_token", ctypes.c_int64),
         ("scale", ctypes.c_double),
+        ("q_len", ctypes.c_int),
     ]
 
 
@@ -79,7 +80,12 @@ def _dtype_code(a):
 
 
 def _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, strides, keep):
+    q_len = 1
+    if q.ndim == 4:  # multi-query form [B][q_len][Hq][d]
+        q_len = q.shape[1]
+        q = q.reshape(q.shape[0], q_len * q.shape[2], q.shape[3])
     B, Hq, d = q.shape
+    Hq //= q_len
     if k_pool.ndim != 4 or v_pool.shape != k_pool.shape:
         raise ValueError("pools must be [num_phys_blocks][Hkv][T][d]")
     _, Hkv, T, dd = k_pool.shape
@@ -103,16 +109,20 @@ def _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, stri
     p.max_blocks = block_table.shape[1]
     p.stride_block, p.stride_head, p.stride_token = strides
     p.scale = float(scale)
+    p.q_len = q_len
     return p
 
 
 def attention(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale,
               pairs=None, strides=None, n_threads=1):
-    """Eq. 1.  Returns (out, lse) in fp64: [B][Hq][d], [B][Hq]; or [n][d], [n] for ``pairs`` (n x 2: r, h)."""
+    """Eq. 1.  Returns (out, lse) in fp64: [B][Hq][d], [B][Hq]; or [n][d], [n] for ``pairs`` (n x 2: r, h).
+
+    q may also be [B][q_len][Hq][d] (several new tokens per request, causal among them): outputs are then
+    [B][q_len][Hq][d], [B][q_len][Hq], and a pair's second entry is the virtual head t * Hq + h."""
     keep = []
     p = _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, strides, keep)
     if pairs is None:
-        n = p.B * p.Hq
+        n = p.B * p.Hq * p.q_len
         pairs_ptr = None
     else:
         pairs = np.ascontiguousarray(pairs, dtype=np.int32).reshape(-1, 2)
@@ -124,6 +134,8 @@ def attention(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale,
     if rc != 0:
         raise ValueError("oracle_attention rejected its arguments")
     if pairs is None:
+        if p.q_len > 1 or q.ndim == 4:
+            return out.reshape(p.B, p.q_len, p.Hq, p.d), lse.reshape(p.B, p.q_len, p.Hq)
         return out.reshape(p.B, p.Hq, p.d), lse.reshape(p.B, p.Hq)
     return out, lse
 
@@ -140,7 +152,7 @@ def micro_attention(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scal
     p = _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, strides, keep)
     nparts = np.array([len(b) - 1 for b in bounds], dtype=np.int32)
     flat = np.ascontiguousarray(np.concatenate([np.asarray(b, dtype=np.int64) for b in bounds]))
-    rows = int(nparts.sum()) * p.Hq
+    rows = int(nparts.sum()) * p.Hq * p.q_len
     MA = np.empty((rows, p.d), dtype=np.float64)
     m = np.empty((rows,), dtype=np.float64)
     e = np.empty((rows,), dtype=np.float64)

@@ -17,6 +17,14 @@
  *   oracle_aggregate        Section 4, the unnumbered m_g / e_g equation and
  *                           Eq. 3: aggregation of b partial results.
  *
+ * Multi-query form (several new tokens per request, e.g. speculative decoding
+ * or chunked prefill; Section 2.1 describes prefill and decode, Section 3 says
+ * the partition may be of arbitrary length): q is [B][q_len][Hq][d], the cache
+ * already holds all q_len new tokens, and query t of a request of length L
+ * attends to the tokens i < L - (q_len - 1 - t), i.e. causally.  A "virtual
+ * head" index vh = t * Hq + h addresses the (query token, q-head) pairs, so
+ * outputs are [B][q_len * Hq][d]; q_len = 1 is plain decode.
+ *
  * Readings of the paper adopted here (it is silent on each):
  *   - scores are scale * (q . k_i); the equations print a bare QK_i^T;
  *   - one query per request (decode); it attends to every cached token
@@ -60,7 +68,16 @@ typedef struct {
     int B, Hq, Hkv, d, T, max_blocks;
     int64_t stride_block, stride_head, stride_token;
     double scale;
+    int q_len;               /* query tokens per request, >= 1 */
 } oracle_problem;
+
+/* Tokens that virtual head vh = t * Hq + h of request r may see. */
+static int64_t visible_tokens(const oracle_problem *p, int r, int vh)
+{
+    int t = vh / p->Hq;
+    int64_t n = (int64_t)p->seq_lens[r] - (p->q_len - 1 - t);
+    return n > 0 ? n : 0;
+}
 
 /* Element offset of logical token i of request r, kv-head g, in a pool. */
 static int64_t token_offset(const oracle_problem *p, int r, int g, int64_t i)
@@ -71,12 +88,12 @@ static int64_t token_offset(const oracle_problem *p, int r, int g, int64_t i)
     return pb * p->stride_block + (int64_t)g * p->stride_head + slot * p->stride_token;
 }
 
-/* s_i = scale * sum_c q[r][h][c] * K_i[c] */
-static double score(const oracle_problem *p, int r, int h, int64_t i)
+/* s_i = scale * sum_c q[r][t][h][c] * K_i[c], with vh = t * Hq + h */
+static double score(const oracle_problem *p, int r, int vh, int64_t i)
 {
-    int g = h / (p->Hq / p->Hkv);
+    int g = (vh % p->Hq) / (p->Hq / p->Hkv);
     int64_t koff = token_offset(p, r, g, i);
-    int64_t qoff = ((int64_t)r * p->Hq + h) * p->d;
+    int64_t qoff = ((int64_t)r * p->q_len * p->Hq + vh) * p->d;
     double acc = 0.0;
     for (int c = 0; c < p->d; ++c)
         acc += widen(p->q, p->q_dtype, qoff + c) * widen(p->k_pool, p->kv_dtype, koff + c);
@@ -94,18 +111,19 @@ static double score(const oracle_problem *p, int r, int h, int64_t i)
 int oracle_attention(const oracle_problem *p, const int32_t *pairs, int64_t n_pairs,
                      double *out, double *lse, int n_threads)
 {
-    if (!p || !out || p->Hkv <= 0 || p->Hq % p->Hkv != 0 || p->T <= 0)
+    if (!p || !out || p->Hkv <= 0 || p->Hq % p->Hkv != 0 || p->T <= 0 || p->q_len < 1)
         return 1;
+    const int VH = p->q_len * p->Hq; /* virtual heads per request */
     if (!pairs)
-        n_pairs = (int64_t)p->B * p->Hq;
+        n_pairs = (int64_t)p->B * VH;
     if (n_threads < 1)
         n_threads = 1;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
     for (int64_t w = 0; w < n_pairs; ++w) {
-        int r = pairs ? pairs[2 * w] : (int)(w / p->Hq);
-        int h = pairs ? pairs[2 * w + 1] : (int)(w % p->Hq);
-        int g = h / (p->Hq / p->Hkv);
-        int64_t L = p->seq_lens[r];
+        int r = pairs ? pairs[2 * w] : (int)(w / VH);
+        int h = pairs ? pairs[2 * w + 1] : (int)(w % VH);
+        int g = (h % p->Hq) / (p->Hq / p->Hkv);
+        int64_t L = visible_tokens(p, r, h);
         double *o = out + w * p->d;
         for (int c = 0; c < p->d; ++c)
             o[c] = 0.0;
@@ -145,30 +163,34 @@ int oracle_attention(const oracle_problem *p, const int32_t *pairs, int64_t n_pa
  * boff[r] = sum_{r' < r} (nparts[r'] + 1).  Boundaries need not be multiples
  * of the block size.  Results land in row
  *   row(r, h, j) = Hq * sum_{r' < r} nparts[r']  +  h * nparts[r]  +  j
- * of MA [rows][d], m [rows], e [rows]:
+ * (Hq counts virtual heads, q_len * Hq, in the multi-query form) of MA [rows][d], m [rows], e [rows]:
  *   m_j = max_i s_i,  e_j = sum_i exp(s_i - m_j),  MA_j = sum_i exp(s_i - m_j) V_i
  * (un-normalised, as printed).
  */
 int oracle_micro_attention(const oracle_problem *p, const int32_t *nparts, const int64_t *bounds,
                            double *MA, double *m, double *e, int n_threads)
 {
-    if (!p || !nparts || !bounds || !MA || !m || !e || p->Hkv <= 0 || p->Hq % p->Hkv != 0)
+    if (!p || !nparts || !bounds || !MA || !m || !e || p->Hkv <= 0 || p->Hq % p->Hkv != 0 || p->q_len < 1)
         return 1;
     if (n_threads < 1)
         n_threads = 1;
-    int64_t n_pairs = (int64_t)p->B * p->Hq;
+    const int VH = p->q_len * p->Hq;
+    int64_t n_pairs = (int64_t)p->B * VH;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
     for (int64_t w = 0; w < n_pairs; ++w) {
-        int r = (int)(w / p->Hq), h = (int)(w % p->Hq);
-        int g = h / (p->Hq / p->Hkv);
+        int r = (int)(w / VH), h = (int)(w % VH);
+        int g = (h % p->Hq) / (p->Hq / p->Hkv);
+        int64_t vis = visible_tokens(p, r, h);
         int64_t row0 = 0, boff = 0;
         for (int rr = 0; rr < r; ++rr) {
-            row0 += (int64_t)p->Hq * nparts[rr];
+            row0 += (int64_t)VH * nparts[rr];
             boff += nparts[rr] + 1;
         }
         row0 += (int64_t)h * nparts[r];
         for (int j = 0; j < nparts[r]; ++j) {
             int64_t lo = bounds[boff + j], hi = bounds[boff + j + 1];
+            if (hi > vis)
+                hi = vis; /* causal limit of this query token */
             double *o = MA + (row0 + j) * p->d;
             for (int c = 0; c < p->d; ++c)
                 o[c] = 0.0;

@@ -86,6 +86,7 @@ def main():
     ap.add_argument("--len-div", type=int, default=1, help="divide every length (debug only; result is not the named workload)")
     ap.add_argument("--blocks-per-split", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 VALU, 2 MFMA")
+    ap.add_argument("--q-len", type=int, default=1, help="query tokens per request (1 = decode, the headline metric)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
     ap.add_argument("--no-parity", action="store_true")
     args = ap.parse_args()
@@ -107,6 +108,10 @@ def main():
     torch.cuda.set_device(0)
 
     w = synth.make(synth.recipe(args.workload, len_div=args.len_div), dev)
+    if args.q_len > 1:  # multi-query form: every request brings q_len new tokens (already in the cache)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(4242)
+        w["q"] = torch.randn((w["B"], args.q_len, w["Hq"], 128), device=dev, generator=gen).to(w["q"].dtype)
     prob = da.make_problem(w["q"], w["k_pool"], w["block_table"], w["scale"])
     lens_list = w["seq_lens_host"].tolist()
     plan = da.Plan(prob, lens_list, blocks_per_split=args.blocks_per_split, kernel=args.kernel)
@@ -116,8 +121,9 @@ def main():
     part_o = torch.empty((n, 128), dtype=torch.float32, device=dev)
     part_m = torch.empty((n,), dtype=torch.float32, device=dev)
     part_e = torch.empty((n,), dtype=torch.float32, device=dev)
-    out = torch.empty((w["B"], w["Hq"], 128), dtype=torch.float32, device=dev)
-    lse = torch.empty((w["B"], w["Hq"]), dtype=torch.float32, device=dev)
+    oshape = (w["B"], w["Hq"]) if args.q_len <= 1 else (w["B"], args.q_len, w["Hq"])
+    out = torch.empty(oshape + (128,), dtype=torch.float32, device=dev)
+    lse = torch.empty(oshape, dtype=torch.float32, device=dev)
     lens_c = (ctypes.c_int32 * w["B"])(*lens_list)
     stream = torch.cuda.current_stream()
     sptr = ctypes.c_void_p(stream.cuda_stream)
@@ -170,20 +176,20 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w["name"], "kv_storage": w["dtype"], "batch": w["B"], "q_heads": w["Hq"], "kv_heads": w["Hkv"], "head_dim": 128,
+        "config": {"workload": w["name"], "q_len": args.q_len, "kv_storage": w["dtype"], "batch": w["B"], "q_heads": w["Hq"], "kv_heads": w["Hkv"], "head_dim": 128,
                    "block_tokens": w["T"], "tokens_total": int(w["seq_lens_host"].sum()),
                    "max_len": int(w["seq_lens_host"].max()), "kv_bytes": int(kv_bytes),
                    "work_items": sched["num_items"], "workgroups": sched["workgroups"], "partials": sched["num_partials"],
                    "kernel": sched["kernel"]},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
-        "decode_tokens_per_s_per_layer": round(w["B"] / (ms_per_step * 1e-3), 1),
+        "decode_tokens_per_s_per_layer": round(w["B"] * max(1, args.q_len) / (ms_per_step * 1e-3), 1),
         "fused_da_attention_ms": round(fused_ms, 4),
         "roofline": {"bound": "hbm", "kernel": "micro_attention", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "kernel_ms": round(kern_ms, 4),
                      "traffic": parse_traffic(args.workload)},
     }
 
-    if args.cpu_budget > 0:
+    if args.cpu_budget > 0 and args.q_len <= 1:
         host = dict(q=synth.as_numpy(w["q"]), k_pool=synth.as_numpy(w["k_pool"]), v_pool=synth.as_numpy(w["v_pool"]),
                     block_table=w["block_table_host"], seq_lens=w["seq_lens_host"])
         threads = min(16, len(os.sched_getaffinity(0)))

@@ -46,6 +46,17 @@
  * query attends to all seq_lens[r] cached tokens (no causal mask: decode).  An
  * empty request yields out = 0 and lse = -inf; an empty split yields m = -inf,
  * e = 0, MA = 0 and has weight 0 in the aggregation.
+ *
+ * Multi-query form (da_problem.q_len = n > 1: several new tokens per request,
+ * as in speculative decoding or chunked prefill; Section 2.1, Section 3): q is
+ * [batch][n][num_q_heads][head_dim], the cache already holds the n new tokens,
+ * and query token t attends causally to the tokens i < seq_lens[r] - (n-1-t).
+ * Every (t, h) pair behaves like a q-head of its own, "virtual head"
+ * vh = t * num_q_heads + h: out is [batch][n][num_q_heads][head_dim], lse
+ * [batch][n][num_q_heads], and partial rows are
+ *   row(r, vh, j) = n * num_q_heads * sum_{r' < r} nsplits[r'] + vh * nsplits[r] + j.
+ * A query token that precedes the start of the cache sees nothing (out = 0,
+ * lse = -inf).
  */
 #ifndef DISTATTN_H
 #define DISTATTN_H
@@ -89,6 +100,7 @@ typedef struct {
     int64_t kv_block_stride;    /* elements between physical blocks */
     int64_t kv_head_stride;     /* elements between kv-heads inside a block */
     int64_t kv_token_stride;    /* elements between slots; >= head_dim */
+    int32_t q_len;              /* query tokens per request: 1 (or 0) = decode; up to 128 for the multi-query form */
 } da_problem;
 
 /* Scheduling knobs; a NULL da_tuning* or a zero field means "choose". */

@@ -129,6 +129,8 @@ void fill_micro(const da_plan *pl, da::MicroParams &mp)
     mp.head_tile = pl->sched.head_tile;
     mp.head_tiles = pl->sched.head_tiles;
     mp.per_split = p.num_kv_heads * pl->sched.head_tiles;
+    mp.q_len = p.q_len > 0 ? p.q_len : 1;
+    mp.cols = mp.q_len * mp.G;
     mp.q_bf16 = p.q_dtype == DA_BF16;
     mp.stride_block = p.kv_block_stride;
     mp.stride_head = p.kv_head_stride;
@@ -152,7 +154,7 @@ void fill_combine(const da_plan *pl, da::CombineParams &cp)
     cp.nsplits = (const int32_t *)(pl->dev + lay.nsplits);
     cp.row_base = (const int64_t *)(pl->dev + lay.row_base);
     cp.B = pl->problem.batch;
-    cp.Hq = pl->problem.num_q_heads;
+    cp.Hq = pl->problem.num_q_heads * (pl->problem.q_len > 0 ? pl->problem.q_len : 1);  // virtual heads
     cp.col_slices = ((int64_t)cp.B * cp.Hq < 1024) ? 4 : 1;
 }
 

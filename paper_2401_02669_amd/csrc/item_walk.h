@@ -20,6 +20,26 @@ __device__ __forceinline__ T table_load(const T *p, int64_t i)
     return ((cptr)(uintptr_t)p)[i];
 }
 
+// Column c of a kv-head's group (c < cols = q_len * G) is query token c / G and q-head c % G of the group.
+struct Column {
+    int live;     // c < cols
+    int t, g;     // query token, head inside the group
+    int vh;       // virtual head t * Hq + kvh * G + g: row of q / out inside the request, partial-row group
+    int visible;  // tokens this query may see: L - (q_len - 1 - t), clamped at 0 (causal)
+};
+__device__ __forceinline__ Column column_of(const MicroParams &p, int c, int kvh, int L)
+{
+    Column col;
+    col.live = c < p.cols;
+    const int cc = col.live ? c : 0;
+    col.t = cc / p.G;
+    col.g = cc - col.t * p.G;
+    col.vh = col.t * p.Hq + kvh * p.G + col.g;
+    const int vis = L - (p.q_len - 1 - col.t);
+    col.visible = vis > 0 ? vis : 0;
+    return col;
+}
+
 struct ItemInfo {
     int valid;       // 0: past the end of the item list
     int r, j, kvh, ht, ns;
@@ -34,6 +54,7 @@ struct Chunk {
     int blk;     // logical block
     int cib;     // chunk inside the block
     int lim;     // valid tokens from the chunk's first row on (<= 0: none)
+    int tok0;    // logical token index of the chunk's first row
     int64_t off; // element offset of the chunk's first row (this item's kv-head) inside a pool;
                  // 0 (always readable) when the chunk holds no valid token
 };
@@ -103,6 +124,7 @@ __device__ __forceinline__ void locate_chunk(const MicroParams &p, const ItemInf
 {
     ch.lim = 0;
     ch.off = 0;
+    ch.tok0 = 0;
     if (!ch.valid) return;
     const int pb = table_load(p.block_table, (int64_t)it.r * p.max_blocks + ch.blk);
     const int first = ch.cib * CH;
@@ -113,6 +135,7 @@ __device__ __forceinline__ void locate_chunk(const MicroParams &p, const ItemInf
         valid = 0;
     }
     ch.lim = valid;
+    ch.tok0 = ch.blk * p.T + first;
     if (valid > 0)
         ch.off = (int64_t)pb * p.stride_block + (int64_t)it.kvh * p.stride_head + (int64_t)first * p.stride_token;
 }
@@ -148,3 +171,4 @@ __device__ __forceinline__ Chunk next_chunk(const MicroParams &p, const ItemInfo
 }
 
 }  // namespace da
+

@@ -36,11 +36,13 @@ struct MicroParams {
     const int32_t *range_start;  // [ranges + 1]
     int32_t *err_flag;
     int32_t B, Hq, Hkv, G, T, max_blocks, num_phys;
-    int32_t head_tile;          // q-heads served per work item
-    int32_t head_tiles;         // ceil(G / head_tile)
+    int32_t head_tile;          // columns served per work item
+    int32_t head_tiles;         // ceil(cols / head_tile)
     int32_t q_bf16;
     int32_t direct_out;
     int32_t per_split;          // Hkv * head_tiles
+    int32_t q_len;              // query tokens per request
+    int32_t cols;               // (query token, q-head) columns per kv-head: q_len * G
     int64_t stride_block, stride_head, stride_token;  // elements
     float scale_log2e;          // scale * log2(e): scores are kept in base-2 units inside the kernels
 };

@@ -16,7 +16,9 @@
 //                   v_perm_b32; B = P^T, which is exactly how the lane already holds P.  P is split
 //                   into bf16 high + low parts (two MFMAs) so that it keeps 16 bits of mantissa.
 //
-// Heads beyond the group (lanes with lane % 16 >= G) carry q = 0 and are never written.
+// The 16 columns of a work item are (query token, q-head) pairs of the kv-head's group: q-heads for
+// plain decode, query tokens x q-heads in the multi-query form, where each column also has its own
+// causal limit.  Columns past the group (lane % 16 >= cols) carry q = 0 and are never written.
 #include <hip/hip_runtime.h>
 
 #include "item_walk.h"
@@ -103,11 +105,13 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
             dst[jj] = load16_stream(base + off);
         }
     };
-    // Q^T operand of an item: head = ln, k-slice lg of each of the 4 k-steps (zero for heads past the group)
-    auto load_q = [&](const ItemInfo &it, u32x4 (&dst)[4]) {
-        const int hl = it.ht * kHeadTile + ln;
-        const bool live = it.valid && hl < p.G;
-        const uint16_t *q = (const uint16_t *)p.q + ((int64_t)it.r * p.Hq + (int64_t)it.kvh * p.G + (live ? hl : 0)) * kHeadDim;
+    // Q^T operand of an item: column (query token, q-head) = ln, k-slice lg of each of the 4 k-steps
+    // (zero for columns past the group); also the number of tokens that column may see (causal limit)
+    auto load_q = [&](const ItemInfo &it, u32x4 (&dst)[4], int &visible) {
+        const Column col = column_of(p, it.ht * kHeadTile + ln, it.kvh, it.L);
+        const bool live = it.valid && col.live;
+        visible = live ? col.visible : 0;
+        const uint16_t *q = (const uint16_t *)p.q + ((int64_t)it.r * p.q_len * p.Hq + col.vh) * kHeadDim;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             dst[ks] = u32x4{0u, 0u, 0u, 0u};
@@ -126,8 +130,9 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
     ItemInfo it = decode_item<kChunk>(p, e_begin, e_end, kvh, ht);
     Chunk cur = first_chunk<kChunk>(p, it, wave, lane);
     u32x4 kr[8], vr[8], qreg[4];
+    int visible = 0, visible_next = 0;  // causal limit of this lane's column, for the current / next item
     load_k(fetch_of(cur), kr);
-    load_q(it, qreg);
+    load_q(it, qreg, visible);
 
     while (it.valid) {
         float m = kNegInf;   // running maximum of head ln's scores, base-2 units (all lane groups agree)
@@ -165,10 +170,11 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
 
             // scores in base-2 units (scale * log2(e) applied), rows past the valid tokens masked out
             float s[8];
+            const int rows_seen = min(cur.lim, visible - cur.tok0);  // rows of this chunk the column may see
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                s[i] = (4 * lg + i < cur.lim) ? s0[i] * c2 : kNegInf;
-                s[4 + i] = (16 + 4 * lg + i < cur.lim) ? s1[i] * c2 : kNegInf;
+                s[i] = (4 * lg + i < rows_seen) ? s0[i] * c2 : kNegInf;
+                s[4 + i] = (16 + 4 * lg + i < rows_seen) ? s1[i] * c2 : kNegInf;
             }
             float cm = s[0];
 #pragma unroll
@@ -225,13 +231,12 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
         }
         // the last step above requested the first K chunk of the next item
         if (idle) load_k(fetch_of(ncur), kr);
-        load_q(nit, qreg);
+        load_q(nit, qreg, visible_next);
 
         // ---- wavefront result: exp-sum over the lane groups; m is already common -----------------
-        const int hl = it.ht * kHeadTile + ln;
         e += __shfl_xor(e, 16);
         e += __shfl_xor(e, 32);
-        if (hl < p.G) {
+        if (it.ht * kHeadTile + ln < p.cols) {
             if (lg == 0) {
                 lds_m[buf][wave][ln] = m;
                 lds_e[buf][wave][ln] = e;
@@ -247,7 +252,7 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
 
         // ---- merge the wavefronts and write the item's result -------------------------------------
         const bool direct = p.direct_out && it.ns == 1;
-        int heads = p.G - it.ht * kHeadTile;
+        int heads = p.cols - it.ht * kHeadTile;
         heads = heads > kHeadTile ? kHeadTile : heads;
         for (int idx = tid; idx < heads * kHeadDim; idx += kWaves * 64) {
             const int g = idx / kHeadDim, col = idx % kHeadDim;
@@ -262,14 +267,14 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
                 o = fmaf(lds_o[buf][w][g][col], wgt, o);
                 E = fmaf(lds_e[buf][w][g], wgt, E);
             }
-            const int h = it.kvh * p.G + it.ht * kHeadTile + g;
+            const int vh = column_of(p, it.ht * kHeadTile + g, it.kvh, it.L).vh;
             const float m_nat = M * kLn2;  // base-2 -> natural-log score units (-inf stays -inf)
             if (direct) {
-                const int64_t orow = (int64_t)it.r * p.Hq + h;
+                const int64_t orow = (int64_t)it.r * p.q_len * p.Hq + vh;
                 p.out[orow * kHeadDim + col] = (E > 0.0f) ? o / E : 0.0f;
                 if (col == 0 && p.lse) p.lse[orow] = (E > 0.0f) ? m_nat + __logf(E) : kNegInf;
             } else {
-                const int64_t prow = it.row_base + (int64_t)h * it.ns + it.j;
+                const int64_t prow = it.row_base + (int64_t)vh * it.ns + it.j;
                 p.part_o[prow * kHeadDim + col] = o;
                 if (col == 0) {
                     p.part_m[prow] = m_nat;
@@ -277,6 +282,7 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
                 }
             }
         }
+        visible = visible_next;
         it = nit;
         cur = ncur;
     }

@@ -1,7 +1,7 @@
 // MicroAttention on the fp32 vector ALU (Section 4, m_j / e_j equation and Eq. 2).
 //
-// A work item is a run of tokens of one (request, kv-head) and up to GT q-heads of that kv-head's
-// group.  The launch is persistent: each workgroup (4 wavefronts) walks its items one after the
+// A work item is a run of tokens of one (request, kv-head) and up to GT columns of that kv-head's
+// group (q-heads for plain decode; query tokens x q-heads, each with a causal limit, otherwise).  The launch is persistent: each workgroup (4 wavefronts) walks its items one after the
 // other and requests the next item's first K chunk before merging and writing the current item's
 // result.  Wavefront w takes chunks w, w + 4, ... of the item.  A load instruction fetches 1 KiB of
 // consecutive K (or V) bytes: RPL whole token rows, LPR lanes per row, 16 bytes per lane.  Each
@@ -117,13 +117,15 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
             dst[jj] = load16_stream(base + off);
         }
     };
-    // this lane's slice of the item's queries, pre-scaled to base-2 units (zero for heads past the group)
-    auto load_q = [&](const ItemInfo &it, float (&qf)[GT][EPL]) {
+    // this lane's slice of the item's queries, pre-scaled to base-2 units (zero for columns past the group),
+    // and the number of tokens each column may see (causal limit of its query token)
+    auto load_q = [&](const ItemInfo &it, float (&qf)[GT][EPL], int (&visible)[GT]) {
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
-            const int hl = it.ht * GT + g;
-            const bool live = it.valid && hl < p.G;
-            const int64_t qoff = ((int64_t)it.r * p.Hq + (int64_t)it.kvh * p.G + (live ? hl : 0)) * kHeadDim + colc * EPL;
+            const Column col = column_of(p, it.ht * GT + g, it.kvh, it.L);
+            const bool live = it.valid && col.live;
+            visible[g] = live ? col.visible : 0;
+            const int64_t qoff = ((int64_t)it.r * p.q_len * p.Hq + col.vh) * kHeadDim + colc * EPL;
             float x[EPL];
             if (p.q_bf16) {
                 uint32_t w[EPL / 2];
@@ -157,8 +159,9 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
     Chunk cur = first_chunk<CH>(p, it, wave, lane);
     u32x4 kr[NL], vr[NL];
     float qf[GT][EPL];
+    int visible[GT], visible_next[GT];  // causal limits of the columns, for the current / next item
     load_rows(kbase, fetch_of(cur), kr);
-    load_q(it, qf);
+    load_q(it, qf, visible);
 
     while (it.valid) {
         float m[GT], e[GT], o[GT][EPL];
@@ -186,18 +189,20 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
 
             // scores of the chunk's rows, base-2 units
             float s[NL][GT];
+            int rows_seen[GT];  // rows of this chunk each column may see
+#pragma unroll
+            for (int g = 0; g < GT; ++g) rows_seen[g] = min(cur.lim, visible[g] - cur.tok0);
 #pragma unroll
             for (int jj = 0; jj < NL; ++jj) {
                 float kf[EPL];
                 Slice<KVBF16>::unpack(kr[jj], kf);
-                const bool valid = jj * RPL + row < cur.lim;
 #pragma unroll
                 for (int g = 0; g < GT; ++g) {
                     float acc = 0.0f;
 #pragma unroll
                     for (int c = 0; c < EPL; ++c) acc = fmaf(qf[g][c], kf[c], acc);
                     acc = (LPR == 16) ? row16_sum(acc) : row32_sum(acc);
-                    s[jj][g] = valid ? acc : kNegInf;
+                    s[jj][g] = (jj * RPL + row < rows_seen[g]) ? acc : kNegInf;
                 }
             }
             load_rows(kbase, kf_next, kr);
@@ -237,7 +242,7 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
         }
         // the last step above requested the first K chunk of the next item
         if (idle) load_rows(kbase, fetch_of(ncur), kr);
-        load_q(nit, qf);
+        load_q(nit, qf, visible_next);
 
         // ---- merge the RPL row positions of the wavefront --------------------------------------
 #pragma unroll
@@ -272,8 +277,8 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
         const bool direct = p.direct_out && it.ns == 1;
         for (int idx = tid; idx < GT * kHeadDim; idx += kWaves * 64) {
             const int g = idx / kHeadDim, col = idx % kHeadDim;
-            const int hl = it.ht * GT + g;
-            if (hl >= p.G) continue;
+            const Column cc = column_of(p, it.ht * GT + g, it.kvh, it.L);
+            if (!cc.live) continue;
             float M = lds_m[buf][0][g];
 #pragma unroll
             for (int w = 1; w < kWaves; ++w) M = fmaxf(M, lds_m[buf][w][g]);
@@ -285,13 +290,12 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
                 acc = fmaf(lds_o[buf][w][g][col], wgt, acc);
                 E = fmaf(lds_e[buf][w][g], wgt, E);
             }
-            const int h = it.kvh * p.G + hl;
             if (direct) {
-                const int64_t orow = (int64_t)it.r * p.Hq + h;
+                const int64_t orow = (int64_t)it.r * p.q_len * p.Hq + cc.vh;
                 p.out[orow * kHeadDim + col] = (E > 0.0f) ? acc / E : 0.0f;
                 if (col == 0 && p.lse) p.lse[orow] = (E > 0.0f) ? M * kLn2 + __logf(E) : kNegInf;
             } else {
-                const int64_t prow = it.row_base + (int64_t)h * it.ns + it.j;
+                const int64_t prow = it.row_base + (int64_t)cc.vh * it.ns + it.j;
                 p.part_o[prow * kHeadDim + col] = acc;
                 if (col == 0) {
                     p.part_m[prow] = M * kLn2;  // back to natural-log units (-inf stays -inf)
@@ -299,6 +303,8 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
                 }
             }
         }
+#pragma unroll
+        for (int g = 0; g < GT; ++g) visible[g] = visible_next[g];
         it = nit;
         cur = ncur;
     }

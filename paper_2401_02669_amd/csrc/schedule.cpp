@@ -48,6 +48,8 @@ da_status validate_problem(const da_problem &p)
     if (p.head_dim != 128) return DA_ERR_UNSUPPORTED;
     if (p.block_tokens % 16 != 0) return DA_ERR_UNSUPPORTED;
     if (p.num_q_heads / p.num_kv_heads > 64) return DA_ERR_UNSUPPORTED;
+    if (p.q_len < 0) return DA_ERR_INVALID_ARG;
+    if (p.q_len > 128) return DA_ERR_UNSUPPORTED;
     const int64_t esize = p.kv_dtype == DA_BF16 ? 2 : 4;
     if (p.kv_token_stride < p.head_dim || p.kv_head_stride < 0 || p.kv_block_stride < 0) return DA_ERR_INVALID_ARG;
     if ((p.kv_token_stride * esize) % 16 || (p.kv_head_stride * esize) % 16 || (p.kv_block_stride * esize) % 16)
@@ -67,7 +69,8 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
         return DA_ERR_INVALID_ARG;
 
     const int B = p.batch, T = p.block_tokens;
-    const int G = p.num_q_heads / p.num_kv_heads;
+    const int q_len = p.q_len > 0 ? p.q_len : 1;
+    const int G = (p.num_q_heads / p.num_kv_heads) * q_len;  // (query token, q-head) columns per kv-head
     const int64_t tpb = (T + kTileTokens - 1) / kTileTokens;
 
     // kernel family, head tile, workgroup size
@@ -149,7 +152,7 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
         s.nsplits[r] = (int32_t)cuts[r].size() + 1;
         s.max_nsplits = std::max(s.max_nsplits, s.nsplits[r]);
         s.row_base[r] = rows;
-        rows += (int64_t)s.nsplits[r] * p.num_q_heads;
+        rows += (int64_t)s.nsplits[r] * p.num_q_heads * q_len;
     }
     s.num_partials = rows;
     s.entries.clear();

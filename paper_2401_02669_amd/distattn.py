@@ -32,6 +32,7 @@ class DaProblem(ctypes.Structure):
         ("num_phys_blocks", ctypes.c_int32), ("kv_dtype", ctypes.c_int32), ("q_dtype", ctypes.c_int32),
         ("scale", ctypes.c_float),
         ("kv_block_stride", ctypes.c_int64), ("kv_head_stride", ctypes.c_int64), ("kv_token_stride", ctypes.c_int64),
+        ("q_len", ctypes.c_int32),
     ]
 
 
@@ -101,8 +102,14 @@ def _dtype_code(t):
 
 
 def make_problem(q, k_pool, block_table, scale):
-    """da_problem for q [B][Hq][d] and a pool tensor [P][Hkv][T][d] (any strides with a contiguous last dim)."""
-    B, Hq, d = q.shape
+    """da_problem for q [B][Hq][d] (or [B][q_len][Hq][d]) and a pool tensor [P][Hkv][T][d] (any strides with a
+    contiguous last dim)."""
+    q_len = 1
+    if q.dim() == 4:
+        q_len = q.shape[1]
+        B, _, Hq, d = q.shape
+    else:
+        B, Hq, d = q.shape
     P, Hkv, T, dd = k_pool.shape
     assert dd == d and k_pool.stride(3) == 1 and q.is_contiguous()
     p = DaProblem()
@@ -111,6 +118,7 @@ def make_problem(q, k_pool, block_table, scale):
     p.kv_dtype, p.q_dtype = _dtype_code(k_pool), _dtype_code(q)
     p.scale = float(scale)
     p.kv_block_stride, p.kv_head_stride, p.kv_token_stride = k_pool.stride(0), k_pool.stride(1), k_pool.stride(2)
+    p.q_len = q_len
     return p
 
 
@@ -203,6 +211,10 @@ class Plan:
         _check(lib().da_plan_error(self._h, _stream_ptr(stream), ctypes.byref(f)), "da_plan_error")
         return f.value
 
+    def _out_shape(self):
+        p = self.problem
+        return (p.batch, p.num_q_heads) if p.q_len <= 1 else (p.batch, p.q_len, p.num_q_heads)
+
     # ---- launches -------------------------------------------------------------------------
     def partial(self, q, k_pool, v_pool, block_table, seq_lens, part_o=None, part_m=None, part_e=None, stream=None):
         if part_o is None:
@@ -219,8 +231,8 @@ class Plan:
     def combine(self, part_o, part_m, part_e, out=None, lse=None, stream=None):
         p = self.problem
         if out is None:
-            out = torch.empty((p.batch, p.num_q_heads, p.head_dim), dtype=torch.float32, device=part_o.device)
-            lse = torch.empty((p.batch, p.num_q_heads), dtype=torch.float32, device=part_o.device)
+            out = torch.empty(self._out_shape() + (p.head_dim,), dtype=torch.float32, device=part_o.device)
+            lse = torch.empty(self._out_shape(), dtype=torch.float32, device=part_o.device)
         st = lib().da_combine(self._h, _ptr(part_o), _ptr(part_m), _ptr(part_e), _ptr(out), _ptr(lse),
                               _stream_ptr(stream))
         _check(st, "da_combine")
@@ -229,8 +241,8 @@ class Plan:
     def attention(self, q, k_pool, v_pool, block_table, seq_lens, out=None, lse=None, workspace=None, stream=None):
         p = self.problem
         if out is None:
-            out = torch.empty((p.batch, p.num_q_heads, p.head_dim), dtype=torch.float32, device=q.device)
-            lse = torch.empty((p.batch, p.num_q_heads), dtype=torch.float32, device=q.device)
+            out = torch.empty(self._out_shape() + (p.head_dim,), dtype=torch.float32, device=q.device)
+            lse = torch.empty(self._out_shape(), dtype=torch.float32, device=q.device)
         if workspace is None:
             workspace = torch.empty((max(self.workspace_bytes, 256),), dtype=torch.uint8, device=q.device)
         st = lib().da_attention(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table), _ptr(seq_lens),

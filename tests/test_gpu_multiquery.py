@@ -1,0 +1,94 @@
+"""GPU parity of the multi-query (causal) form against the fp64 oracle: several new tokens per request,
+every (query token, q-head) pair a column of its kv-head's group with its own causal limit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2401_02669_amd import distattn as da
+from paper_2401_02669_amd import synth
+from util import TOL, assert_parity, errors
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def make(lens, n, Hq, Hkv, T, dtype="bf16", seed=0):
+    w = synth.make(synth.recipe("c5_mixed", B=len(lens), Hq=Hq, Hkv=Hkv, T=T, dtype=dtype, lens=list(lens)), DEV)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(1000 + seed)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    w["q"] = torch.randn((len(lens), n, Hq, 128), device=DEV, generator=gen).to(tdt)
+    return w
+
+
+def run_both(w, **tuning):
+    prob = da.make_problem(w["q"], w["k_pool"], w["block_table"], w["scale"])
+    plan = da.Plan(prob, w["seq_lens_host"].tolist(), **tuning)
+    out, lse = plan.attention(w["q"], w["k_pool"], w["v_pool"], w["block_table"], w["seq_lens"])
+    po, pm, pe = plan.partial(w["q"], w["k_pool"], w["v_pool"], w["block_table"], w["seq_lens"])
+    out2, lse2 = plan.combine(po, pm, pe)
+    torch.cuda.synchronize()
+    assert plan.error_flags() == 0
+    return plan, (out.cpu().numpy(), lse.cpu().numpy()), (out2.cpu().numpy(), lse2.cpu().numpy()), (po, pm, pe)
+
+
+def ref_of(w):
+    return oracle.attention(synth.as_numpy(w["q"]), synth.as_numpy(w["k_pool"]), synth.as_numpy(w["v_pool"]),
+                            w["block_table_host"], w["seq_lens_host"], w["T"], w["scale"], n_threads=16)
+
+
+@pytest.mark.parametrize("n", [2, 3, 4, 16, 17])
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 2), (16, 2)])
+@pytest.mark.parametrize("kernel", [da.DA_KERNEL_AUTO, da.DA_KERNEL_VALU], ids=["auto", "valu"])
+def test_multi_query_matches_oracle(n, Hq, Hkv, kernel):
+    lens = [700, 0, 1, n - 1, n, n + 1, 64, 65, 2049]
+    w = make(lens, n, Hq, Hkv, T=64, seed=n)
+    print("case multi-query n=%d Hq=%d Hkv=%d kernel=%d" % (n, Hq, Hkv, kernel), flush=True)
+    ref_out, ref_lse = ref_of(w)
+    for bps in (0, 3):
+        plan, fused, two_step, _ = run_both(w, kernel=kernel, blocks_per_split=bps)
+        plan.close()
+        for (out, lse), what in ((fused, "fused"), (two_step, "two-step")):
+            assert out.shape == ref_out.shape
+            assert_parity(out, lse, ref_out, ref_lse, "bf16", "%s n=%d bps=%d" % (what, n, bps))
+            # the last query token of the longest request sees everything; the first one misses n - 1 tokens
+            for t in (0, n - 1):
+                _, rel = errors(out[8, t], ref_out[8, t])
+                assert rel <= TOL["bf16"]["rel_l2"]
+
+
+def test_multi_query_fp32_cache():
+    w = make([300, 5, 1000], 3, 4, 2, T=32, dtype="f32")
+    ref_out, ref_lse = ref_of(w)
+    plan, fused, two_step, _ = run_both(w)
+    plan.close()
+    assert_parity(fused[0], fused[1], ref_out, ref_lse, "f32", "fp32 multi-query fused")
+    assert_parity(two_step[0], two_step[1], ref_out, ref_lse, "f32", "fp32 multi-query two-step")
+
+
+@pytest.mark.parametrize("kernel", [da.DA_KERNEL_AUTO, da.DA_KERNEL_VALU], ids=["auto", "valu"])
+def test_multi_query_partials_match_micro_attention(kernel):
+    n, Hq = 4, 4
+    w = make([900, 3, 130], n, Hq, 2, T=32)
+    plan, _, _, (po, pm, pe) = run_both(w, kernel=kernel, blocks_per_split=2)
+    bounds = []
+    for r in range(w["B"]):
+        b = [0]
+        for j in range(plan.nsplits(r)):
+            lo, hi = plan.split(r, j)
+            assert lo == b[-1]
+            b.append(hi)
+        bounds.append(b)
+    plan.close()
+    MA, m, e, nparts = oracle.micro_attention(synth.as_numpy(w["q"]), synth.as_numpy(w["k_pool"]), synth.as_numpy(w["v_pool"]),
+                                              w["block_table_host"], w["seq_lens_host"], w["T"], w["scale"], bounds)
+    po, pm, pe = (x.cpu().numpy().astype(np.float64) for x in (po, pm, pe))
+    assert po.shape[0] == MA.shape[0] == int(nparts.sum()) * n * Hq
+    live = np.isfinite(m)
+    assert np.array_equal(np.isneginf(pm), ~live) and np.all(pe[~live] == 0) and np.all(po[~live] == 0)
+    np.testing.assert_allclose(pm[live], m[live], rtol=0, atol=2e-5)
+    adj = np.exp(pm[live] - m[live])
+    np.testing.assert_allclose(pe[live] * adj, e[live], rtol=2e-4)
+    num = np.linalg.norm(po[live] * adj[:, None] - MA[live], axis=1)
+    assert np.all(num <= 1e-3 * np.linalg.norm(MA[live], axis=1) + 1e-12)

@@ -16,9 +16,10 @@
 //                   v_perm_b32; B = P^T, which is exactly how the lane already holds P.  P is split
 //                   into bf16 high + low parts (two MFMAs) so that it keeps 16 bits of mantissa.
 //
-// The 16 columns of a work item are (query token, q-head) pairs of the kv-head's group: q-heads for
+// The columns of a work item are (query token, q-head) pairs of the kv-head's group: q-heads for
 // plain decode, query tokens x q-heads in the multi-query form, where each column also has its own
-// causal limit.  Columns past the group (lane % 16 >= cols) carry q = 0 and are never written.
+// causal limit.  A work item serves TILES (1 or 2) tiles of 16 columns from one K/V read.  Columns
+// past the group carry q = 0 and are never written.
 #include <hip/hip_runtime.h>
 
 #include "item_walk.h"
@@ -35,7 +36,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kNegInf = -__builtin_inff();
 constexpr float kLn2 = 0.69314718055994530942f;
-constexpr int kHeadTile = 16;  // q-heads per work item (MFMA N dimension)
+constexpr int kHeadTile = 16;  // columns per MFMA tile (N dimension)
 constexpr int kChunk = 32;     // tokens per wavefront step (MFMA K dimension of the PV product)
 constexpr int kWaves = 4;      // wavefronts per workgroup
 
@@ -58,12 +59,14 @@ __device__ __forceinline__ f32x4 mfma_bf16(const u32x4 &a, const u32x4 &b, f32x4
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+template <int TILES>
 __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const MicroParams p)
 {
-    // cross-wavefront merge buffers, two sets used alternately by consecutive items
-    __shared__ float lds_m[2][kWaves][kHeadTile];
-    __shared__ float lds_e[2][kWaves][kHeadTile];
-    __shared__ float lds_o[2][kWaves][kHeadTile][kHeadDim];
+    constexpr int COLS = kHeadTile * TILES;  // columns per work item
+    // cross-wavefront merge buffers (one barrier after they are written, one after they are read)
+    __shared__ float lds_m[kWaves][COLS];
+    __shared__ float lds_e[kWaves][COLS];
+    __shared__ float lds_o[kWaves][COLS][kHeadDim];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -107,15 +110,18 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
     };
     // Q^T operand of an item: column (query token, q-head) = ln, k-slice lg of each of the 4 k-steps
     // (zero for columns past the group); also the number of tokens that column may see (causal limit)
-    auto load_q = [&](const ItemInfo &it, u32x4 (&dst)[4], int &visible) {
-        const Column col = column_of(p, it.ht * kHeadTile + ln, it.kvh, it.L);
-        const bool live = it.valid && col.live;
-        visible = live ? col.visible : 0;
-        const uint16_t *q = (const uint16_t *)p.q + ((int64_t)it.r * p.q_len * p.Hq + col.vh) * kHeadDim;
+    auto load_q = [&](const ItemInfo &it, u32x4 (&dst)[TILES][4], int (&visible)[TILES]) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            dst[ks] = u32x4{0u, 0u, 0u, 0u};
-            if (live) dst[ks] = *(const u32x4 *)(q + ks * 32 + lg * 8);
+        for (int tl = 0; tl < TILES; ++tl) {
+            const Column col = column_of(p, it.ht * COLS + tl * kHeadTile + ln, it.kvh, it.L);
+            const bool live = it.valid && col.live;
+            visible[tl] = live ? col.visible : 0;
+            const uint16_t *q = (const uint16_t *)p.q + ((int64_t)it.r * p.q_len * p.Hq + col.vh) * kHeadDim;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                dst[tl][ks] = u32x4{0u, 0u, 0u, 0u};
+                if (live) dst[tl][ks] = *(const u32x4 *)(q + ks * 32 + lg * 8);
+            }
         }
     };
 
@@ -129,21 +135,25 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
     int round = 0;
     ItemInfo it = decode_item<kChunk>(p, e_begin, e_end, kvh, ht);
     Chunk cur = first_chunk<kChunk>(p, it, wave, lane);
-    u32x4 kr[8], vr[8], qreg[4];
-    int visible = 0, visible_next = 0;  // causal limit of this lane's column, for the current / next item
+    u32x4 kr[8], vr[8], qreg[TILES][4];
+    int visible[TILES], visible_next[TILES];  // causal limits of this lane's columns, for the current / next item
     load_k(fetch_of(cur), kr);
     load_q(it, qreg, visible);
 
     while (it.valid) {
-        float m = kNegInf;   // running maximum of head ln's scores, base-2 units (all lane groups agree)
-        float e = 0.0f;      // this lane's share of the exp-sum (its 8 tokens per chunk)
-        f32x4 acc[8];        // O^T: acc[n][i] = O[head ln][column 32*lg + 8*i + n]
+        float m[TILES];      // running maximum of column ln's scores, base-2 units (all lane groups agree)
+        float e[TILES];      // this lane's share of the exp-sum (its 8 tokens per chunk)
+        f32x4 acc[TILES][8]; // O^T: acc[tl][n][i] = O[column ln of tile tl][dim 32*lg + 8*i + n]
 #pragma unroll
-        for (int n = 0; n < 8; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int tl = 0; tl < TILES; ++tl) {
+            m[tl] = kNegInf;
+            e[tl] = 0.0f;
+#pragma unroll
+            for (int n = 0; n < 8; ++n) acc[tl][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
 
         // the item after this one is looked up early, so that its first K chunk can be requested
         // before this item's result is merged
-        const int buf = round & 1;
         ++round;
         const ItemInfo nit = decode_item<kChunk>(p, e_begin + round, e_end, kvh, ht);
         const Chunk ncur = first_chunk<kChunk>(p, nit, wave, lane);
@@ -155,12 +165,20 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
             const Chunk nxt = next_chunk<kChunk, kWaves>(p, it, cur, lane);
             const Fetch kf_next = fetch_of(nxt.valid ? nxt : ncur);  // nothing left at all: row 0 of the pool
 
-            // S[token 16*mb + 4*lg + i][head ln] for mb = 0, 1
-            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+            // S[token 16*mb + 4*lg + i][column ln] for mb = 0, 1 and every column tile
+            f32x4 s0[TILES], s1[TILES];
+#pragma unroll
+            for (int tl = 0; tl < TILES; ++tl) {
+                s0[tl] = f32x4{0.f, 0.f, 0.f, 0.f};
+                s1[tl] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                s0 = mfma_bf16(kr[ks], qreg[ks], s0);
-                s1 = mfma_bf16(kr[4 + ks], qreg[ks], s1);
+#pragma unroll
+                for (int tl = 0; tl < TILES; ++tl) {
+                    s0[tl] = mfma_bf16(kr[ks], qreg[tl][ks], s0[tl]);
+                    s1[tl] = mfma_bf16(kr[4 + ks], qreg[tl][ks], s1[tl]);
+                }
             }
             load_k(kf_next, kr);
             if (cur.lim <= 0) {  // a chunk slot without valid tokens contributes nothing
@@ -168,38 +186,37 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
                 continue;
             }
 
-            // scores in base-2 units (scale * log2(e) applied), rows past the valid tokens masked out
-            float s[8];
-            const int rows_seen = min(cur.lim, visible - cur.tok0);  // rows of this chunk the column may see
+            u32x4 ph[TILES], pl[TILES];  // P^T operands: 8 tokens of this lane group, column ln; high and low bf16 parts
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                s[i] = (4 * lg + i < rows_seen) ? s0[i] * c2 : kNegInf;
-                s[4 + i] = (16 + 4 * lg + i < rows_seen) ? s1[i] * c2 : kNegInf;
-            }
-            float cm = s[0];
+            for (int tl = 0; tl < TILES; ++tl) {
+                // scores in base-2 units (scale * log2(e) applied); rows past the valid or visible tokens masked out
+                float s[8];
+                const int rows_seen = min(cur.lim, visible[tl] - cur.tok0);
 #pragma unroll
-            for (int i = 1; i < 8; ++i) cm = fmaxf(cm, s[i]);
-            cm = fmaxf(cm, __shfl_xor(cm, 16));
-            cm = fmaxf(cm, __shfl_xor(cm, 32));
-            const float mn = fmaxf(m, cm);
-            const float mu = (mn == kNegInf) ? 0.0f : mn;
-            const float alpha = fast_exp2(m - mu);
-            m = mn;
-            float sum = 0.0f;
+                for (int i = 0; i < 4; ++i) {
+                    s[i] = (4 * lg + i < rows_seen) ? s0[tl][i] * c2 : kNegInf;
+                    s[4 + i] = (16 + 4 * lg + i < rows_seen) ? s1[tl][i] * c2 : kNegInf;
+                }
+                float cm = s[0];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                s[i] = fast_exp2(s[i] - mu);
-                sum += s[i];
-            }
-            e = fmaf(e, alpha, sum);
-            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+                for (int i = 1; i < 8; ++i) cm = fmaxf(cm, s[i]);
+                cm = fmaxf(cm, __shfl_xor(cm, 16));
+                cm = fmaxf(cm, __shfl_xor(cm, 32));
+                const float mn = fmaxf(m[tl], cm);
+                const float mu = (mn == kNegInf) ? 0.0f : mn;
+                const float alpha = fast_exp2(m[tl] - mu);
+                m[tl] = mn;
+                float sum = 0.0f;
 #pragma unroll
-                for (int n = 0; n < 8; ++n) acc[n] *= alpha;
-            }
-
-            // P^T operand: 8 tokens of this lane group, head ln; high and low bf16 parts
-            u32x4 ph, pl;
-            {
+                for (int i = 0; i < 8; ++i) {
+                    s[i] = fast_exp2(s[i] - mu);
+                    sum += s[i];
+                }
+                e[tl] = fmaf(e[tl], alpha, sum);
+                if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                    for (int n = 0; n < 8; ++n) acc[tl][n] *= alpha;
+                }
                 uint32_t h[4], l[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
@@ -208,24 +225,27 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
                     const float r1 = s[2 * t + 1] - as_f(h[t] & 0xFFFF0000u);
                     l[t] = pack_bf16(r0, r1);
                 }
-                ph = u32x4{h[0], h[1], h[2], h[3]};
-                pl = u32x4{l[0], l[1], l[2], l[3]};
+                ph[tl] = u32x4{h[0], h[1], h[2], h[3]};
+                pl[tl] = u32x4{l[0], l[1], l[2], l[3]};
             }
 
-            // O^T += V^T . P^T, 8 MFMA column groups; column group n takes columns 8*m + n, m = MFMA row
+            // O^T += V^T . P^T, 8 MFMA dimension groups; group n takes dims 8*m + n, m = MFMA row
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
                 const uint32_t d0 = vr[0][w], d1 = vr[1][w], d2 = vr[2][w], d3 = vr[3][w];
                 const uint32_t d4 = vr[4][w], d5 = vr[5][w], d6 = vr[6][w], d7 = vr[7][w];
-                // even column 2w: low halves; odd column 2w+1: high halves; (token 2t, token 2t+1) per register
+                // even dim 2w: low halves; odd dim 2w+1: high halves; (token 2t, token 2t+1) per register
                 const u32x4 ve = u32x4{__builtin_amdgcn_perm(d1, d0, 0x05040100u), __builtin_amdgcn_perm(d3, d2, 0x05040100u),
                                        __builtin_amdgcn_perm(d5, d4, 0x05040100u), __builtin_amdgcn_perm(d7, d6, 0x05040100u)};
                 const u32x4 vo = u32x4{__builtin_amdgcn_perm(d1, d0, 0x07060302u), __builtin_amdgcn_perm(d3, d2, 0x07060302u),
                                        __builtin_amdgcn_perm(d5, d4, 0x07060302u), __builtin_amdgcn_perm(d7, d6, 0x07060302u)};
-                acc[2 * w] = mfma_bf16(ve, ph, acc[2 * w]);
-                acc[2 * w] = mfma_bf16(ve, pl, acc[2 * w]);
-                acc[2 * w + 1] = mfma_bf16(vo, ph, acc[2 * w + 1]);
-                acc[2 * w + 1] = mfma_bf16(vo, pl, acc[2 * w + 1]);
+#pragma unroll
+                for (int tl = 0; tl < TILES; ++tl) {
+                    acc[tl][2 * w] = mfma_bf16(ve, ph[tl], acc[tl][2 * w]);
+                    acc[tl][2 * w] = mfma_bf16(ve, pl[tl], acc[tl][2 * w]);
+                    acc[tl][2 * w + 1] = mfma_bf16(vo, ph[tl], acc[tl][2 * w + 1]);
+                    acc[tl][2 * w + 1] = mfma_bf16(vo, pl[tl], acc[tl][2 * w + 1]);
+                }
             }
             cur = nxt;
         }
@@ -234,40 +254,45 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
         load_q(nit, qreg, visible_next);
 
         // ---- wavefront result: exp-sum over the lane groups; m is already common -----------------
-        e += __shfl_xor(e, 16);
-        e += __shfl_xor(e, 32);
-        if (it.ht * kHeadTile + ln < p.cols) {
-            if (lg == 0) {
-                lds_m[buf][wave][ln] = m;
-                lds_e[buf][wave][ln] = e;
-            }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float *dst = &lds_o[buf][wave][ln][32 * lg + 8 * i];
-                *(float4 *)dst = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
-                *(float4 *)(dst + 4) = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
+        for (int tl = 0; tl < TILES; ++tl) {
+            float et = e[tl];
+            et += __shfl_xor(et, 16);
+            et += __shfl_xor(et, 32);
+            const int c = tl * kHeadTile + ln;  // column inside the item
+            if (it.ht * COLS + c < p.cols) {
+                if (lg == 0) {
+                    lds_m[wave][c] = m[tl];
+                    lds_e[wave][c] = et;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float *dst = &lds_o[wave][c][32 * lg + 8 * i];
+                    *(float4 *)dst = make_float4(acc[tl][0][i], acc[tl][1][i], acc[tl][2][i], acc[tl][3][i]);
+                    *(float4 *)(dst + 4) = make_float4(acc[tl][4][i], acc[tl][5][i], acc[tl][6][i], acc[tl][7][i]);
+                }
             }
         }
         __syncthreads();
 
         // ---- merge the wavefronts and write the item's result -------------------------------------
         const bool direct = p.direct_out && it.ns == 1;
-        int heads = p.cols - it.ht * kHeadTile;
-        heads = heads > kHeadTile ? kHeadTile : heads;
+        int heads = p.cols - it.ht * COLS;
+        heads = heads > COLS ? COLS : heads;
         for (int idx = tid; idx < heads * kHeadDim; idx += kWaves * 64) {
             const int g = idx / kHeadDim, col = idx % kHeadDim;
-            float M = lds_m[buf][0][g];
+            float M = lds_m[0][g];
 #pragma unroll
-            for (int w = 1; w < kWaves; ++w) M = fmaxf(M, lds_m[buf][w][g]);
+            for (int w = 1; w < kWaves; ++w) M = fmaxf(M, lds_m[w][g]);
             const float mu = (M == kNegInf) ? 0.0f : M;
             float o = 0.0f, E = 0.0f;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) {
-                const float wgt = fast_exp2(lds_m[buf][w][g] - mu);
-                o = fmaf(lds_o[buf][w][g][col], wgt, o);
-                E = fmaf(lds_e[buf][w][g], wgt, E);
+                const float wgt = fast_exp2(lds_m[w][g] - mu);
+                o = fmaf(lds_o[w][g][col], wgt, o);
+                E = fmaf(lds_e[w][g], wgt, E);
             }
-            const int vh = column_of(p, it.ht * kHeadTile + g, it.kvh, it.L).vh;
+            const int vh = column_of(p, it.ht * COLS + g, it.kvh, it.L).vh;
             const float m_nat = M * kLn2;  // base-2 -> natural-log score units (-inf stays -inf)
             if (direct) {
                 const int64_t orow = (int64_t)it.r * p.q_len * p.Hq + vh;
@@ -282,7 +307,9 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
                 }
             }
         }
-        visible = visible_next;
+        __syncthreads();  // the merge buffers are free again
+#pragma unroll
+        for (int tl = 0; tl < TILES; ++tl) visible[tl] = visible_next[tl];
         it = nit;
         cur = ncur;
     }
@@ -292,8 +319,13 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
 
 hipError_t launch_micro_attention_mfma(const MicroParams &p, int grid, hipStream_t stream)
 {
-    if (p.head_tile != kHeadTile || !p.q_bf16 || grid < 1) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(micro_attention_mfma_kernel, dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+    if (!p.q_bf16 || grid < 1) return hipErrorInvalidValue;
+    if (p.head_tile == kHeadTile)
+        hipLaunchKernelGGL(micro_attention_mfma_kernel<1>, dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+    else if (p.head_tile == 2 * kHeadTile)
+        hipLaunchKernelGGL(micro_attention_mfma_kernel<2>, dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+    else
+        return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

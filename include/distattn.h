@@ -193,6 +193,29 @@ da_status da_combine(const da_plan *plan, const float *part_o, const float *part
                      float *out, float *lse, void *stream);
 
 /*
+ * Aggregation over several partial sets.  Section 4: the intermediate results
+ * of the instances that hold parts of a request's KV cache are brought to the
+ * request's home instance and aggregated there (Eq. 3); Section 5.2: the local
+ * MicroAttention overlaps the remote ones.  Each set is the output of one
+ * da_partial over one share of the batch's KV cache (its own pools, block
+ * table, lengths and plan; all shares have the same batch, heads and q_len and
+ * were given the same queries).  A request's tokens may be divided among the
+ * shares in any way, a share may hold none of them (length 0).  At most 4 sets.
+ * In the multi-query form every share applies the causal rule to its own
+ * length, so only the share holding the newest tokens may have q_len > 1
+ * tokens of them; the tests use q_len = 1.
+ * Launches nothing on the shares' streams: the caller orders `stream` after
+ * the da_partial launches (events) before calling.
+ */
+typedef struct {
+    const da_plan *plan;
+    const float *part_o;
+    const float *part_m;
+    const float *part_e;
+} da_partial_set;
+da_status da_combine_multi(const da_partial_set *sets, int32_t num_sets, float *out, float *lse, void *stream);
+
+/*
  * Fused convenience call: MicroAttention into `workspace`, then aggregation,
  * on one stream = Section 4, Eq. 1.  A request with a single split is
  * normalised inside the MicroAttention kernel and skips the aggregation.

@@ -1,8 +1,10 @@
 // Aggregation of MicroAttention partials (Section 4, m_g / e_g equation and Eq. 3).
 //
 // One workgroup of 256 threads per (request, q-head, column slice).  Pass 1 finds m_g over the
-// nsplits partial maxima; pass 2 accumulates e_j w_j and MA_j w_j with w_j = exp(m_j - m_g), rows
-// spread over the thread rows of the workgroup, float4 columns over its thread columns.
+// partial maxima; pass 2 accumulates e_j w_j and MA_j w_j with w_j = exp(m_j - m_g), rows spread
+// over the thread rows of the workgroup, float4 columns over its thread columns.  The partials may
+// come in several sets (one per KV share of the batch, e.g. local and remote blocks of a request);
+// the sum runs over all of them.
 #include <hip/hip_runtime.h>
 
 #include "kernel_params.h"
@@ -28,15 +30,17 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const CombineP
     const int slice = blockIdx.x % SLICES;
     const int r = pair / p.Hq;
     const int h = pair % p.Hq;
-    const int ns = p.nsplits[r];
-    if (p.skip_single && ns == 1) return;
-    const int64_t row0 = p.row_base[r] + (int64_t)h * ns;
-    const float *pm = p.part_m + row0;
-    const float *pe = p.part_e + row0;
+    int total = 0;
+    for (int s = 0; s < p.num_sets; ++s) total += p.set[s].nsplits[r];
+    if (p.skip_single && p.num_sets == 1 && total == 1) return;
 
     // pass 1: m_g
     float mg = kNegInf;
-    for (int j = tid; j < ns; j += kCombineThreads) mg = fmaxf(mg, pm[j]);
+    for (int s = 0; s < p.num_sets; ++s) {
+        const int ns = p.set[s].nsplits[r];
+        const float *pm = p.set[s].part_m + p.set[s].row_base[r] + (int64_t)h * ns;
+        for (int j = tid; j < ns; j += kCombineThreads) mg = fmaxf(mg, pm[j]);
+    }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) mg = fmaxf(mg, __shfl_xor(mg, off));
     if ((tid & 63) == 0) red[tid >> 6] = mg;
@@ -47,18 +51,24 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const CombineP
     // pass 2: weighted sums
     const int c4 = tid % COLS4;
     const int rw = tid / COLS4;
-    const float4 *po = (const float4 *)(p.part_o + row0 * kHeadDim) + slice * COLS4 + c4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float eg = 0.0f;
-    for (int j = rw; j < ns; j += ROWS) {
-        const float mj = pm[j];
-        const float w = (mj == kNegInf) ? 0.0f : __expf(mj - mu);
-        const float4 v = po[(int64_t)j * (kHeadDim / 4)];
-        eg = fmaf(pe[j], w, eg);
-        acc.x = fmaf(v.x, w, acc.x);
-        acc.y = fmaf(v.y, w, acc.y);
-        acc.z = fmaf(v.z, w, acc.z);
-        acc.w = fmaf(v.w, w, acc.w);
+    for (int s = 0; s < p.num_sets; ++s) {
+        const int ns = p.set[s].nsplits[r];
+        const int64_t row0 = p.set[s].row_base[r] + (int64_t)h * ns;
+        const float *pm = p.set[s].part_m + row0;
+        const float *pe = p.set[s].part_e + row0;
+        const float4 *po = (const float4 *)(p.set[s].part_o + row0 * kHeadDim) + slice * COLS4 + c4;
+        for (int j = rw; j < ns; j += ROWS) {
+            const float mj = pm[j];
+            const float w = (mj == kNegInf) ? 0.0f : __expf(mj - mu);
+            const float4 v = po[(int64_t)j * (kHeadDim / 4)];
+            eg = fmaf(pe[j], w, eg);
+            acc.x = fmaf(v.x, w, acc.x);
+            acc.y = fmaf(v.y, w, acc.y);
+            acc.z = fmaf(v.z, w, acc.z);
+            acc.w = fmaf(v.w, w, acc.w);
+        }
     }
     acc_lds[rw][c4] = acc;
     if (c4 == 0) e_lds[rw] = eg;

@@ -148,11 +148,18 @@ da_status launch_micro(const da_plan *pl, const da::MicroParams &mp, hipStream_t
     return e == hipSuccess ? DA_OK : DA_ERR_HIP;
 }
 
-void fill_combine(const da_plan *pl, da::CombineParams &cp)
+void fill_set(const da_plan *pl, const float *part_o, const float *part_m, const float *part_e, da::PartialSet &ps)
 {
     const TableLayout lay = layout_of(pl);
-    cp.nsplits = (const int32_t *)(pl->dev + lay.nsplits);
-    cp.row_base = (const int64_t *)(pl->dev + lay.row_base);
+    ps.part_o = part_o;
+    ps.part_m = part_m;
+    ps.part_e = part_e;
+    ps.nsplits = (const int32_t *)(pl->dev + lay.nsplits);
+    ps.row_base = (const int64_t *)(pl->dev + lay.row_base);
+}
+
+void fill_combine(const da_plan *pl, da::CombineParams &cp)
+{
     cp.B = pl->problem.batch;
     cp.Hq = pl->problem.num_q_heads * (pl->problem.q_len > 0 ? pl->problem.q_len : 1);  // virtual heads
     cp.col_slices = ((int64_t)cp.B * cp.Hq < 1024) ? 4 : 1;
@@ -348,9 +355,30 @@ da_status da_combine(const da_plan *pl, const float *part_o, const float *part_m
     if (!aligned16(part_o) || !aligned16(out)) return DA_ERR_INVALID_ARG;
     da::CombineParams cp = {};
     fill_combine(pl, cp);
-    cp.part_o = part_o;
-    cp.part_m = part_m;
-    cp.part_e = part_e;
+    fill_set(pl, part_o, part_m, part_e, cp.set[0]);
+    cp.num_sets = 1;
+    cp.out = out;
+    cp.lse = lse;
+    cp.skip_single = 0;
+    return da::launch_combine(cp, (hipStream_t)stream) == hipSuccess ? DA_OK : DA_ERR_HIP;
+}
+
+da_status da_combine_multi(const da_partial_set *sets, int32_t num_sets, float *out, float *lse, void *stream)
+{
+    if (!sets || num_sets < 1 || !out || !aligned16(out)) return DA_ERR_INVALID_ARG;
+    if (num_sets > da::kMaxPartialSets) return DA_ERR_UNSUPPORTED;
+    da::CombineParams cp = {};
+    for (int i = 0; i < num_sets; ++i) {
+        const da_partial_set &s = sets[i];
+        if (!s.plan || !s.part_o || !s.part_m || !s.part_e || !aligned16(s.part_o)) return DA_ERR_INVALID_ARG;
+        const da_problem &a = s.plan->problem, &b = sets[0].plan->problem;
+        // every share describes the same queries: same batch, heads and query tokens
+        if (a.batch != b.batch || a.num_q_heads != b.num_q_heads || (a.q_len > 0 ? a.q_len : 1) != (b.q_len > 0 ? b.q_len : 1))
+            return DA_ERR_INVALID_ARG;
+        fill_set(s.plan, s.part_o, s.part_m, s.part_e, cp.set[i]);
+    }
+    fill_combine(sets[0].plan, cp);
+    cp.num_sets = num_sets;
     cp.out = out;
     cp.lse = lse;
     cp.skip_single = 0;
@@ -391,9 +419,8 @@ da_status da_attention(const da_plan *pl, const void *q, const void *k_pool, con
 
     da::CombineParams cp = {};
     fill_combine(pl, cp);
-    cp.part_o = part_o;
-    cp.part_m = part_m;
-    cp.part_e = part_e;
+    fill_set(pl, part_o, part_m, part_e, cp.set[0]);
+    cp.num_sets = 1;
     cp.out = out;
     cp.lse = lse;
     cp.skip_single = 1;

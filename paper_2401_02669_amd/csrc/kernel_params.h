@@ -47,15 +47,23 @@ struct MicroParams {
     float scale_log2e;          // scale * log2(e): scores are kept in base-2 units inside the kernels
 };
 
-struct CombineParams {
+constexpr int kMaxPartialSets = 4;
+
+// Partials of one MicroAttention launch (one KV share of the batch) as the aggregation reads them.
+struct PartialSet {
     const float *part_o;
     const float *part_m;
     const float *part_e;
+    const int32_t *nsplits;   // [B] of the plan that made them
+    const int64_t *row_base;  // [B]
+};
+
+struct CombineParams {
+    PartialSet set[kMaxPartialSets];
+    int32_t num_sets;
     float *out;
     float *lse;  // may be null
-    const int32_t *nsplits;
-    const int64_t *row_base;
-    int32_t B, Hq;
+    int32_t B, Hq;  // Hq counts virtual heads (q_len * num_q_heads)
     int32_t skip_single;  // requests with one split were already normalised by the MicroAttention kernel
     int32_t col_slices;   // workgroups per (request, q-head), each owning 128 / col_slices columns
 };

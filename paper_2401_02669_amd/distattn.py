@@ -19,7 +19,7 @@ DA_KERNEL_AUTO, DA_KERNEL_VALU, DA_KERNEL_MFMA = 0, 1, 2
 EXPORTS = [
     "da_status_string", "da_plan_schedule", "da_plan_create", "da_plan_update", "da_plan_destroy",
     "da_plan_num_partials", "da_plan_split", "da_plan_nsplits", "da_workspace_bytes", "da_plan_error",
-    "da_partial", "da_combine", "da_attention", "da_probe_read", "da_append",
+    "da_partial", "da_combine", "da_combine_multi", "da_attention", "da_probe_read", "da_append",
     "da_block_pool_create", "da_block_pool_destroy", "da_block_pool_free_count", "da_block_pool_grow",
     "da_block_pool_release",
 ]
@@ -38,6 +38,11 @@ class DaProblem(ctypes.Structure):
 
 class DaTuning(ctypes.Structure):
     _fields_ = [("blocks_per_split", ctypes.c_int32), ("num_cus", ctypes.c_int32), ("kernel", ctypes.c_int32)]
+
+
+class DaPartialSet(ctypes.Structure):
+    _fields_ = [("plan", ctypes.c_void_p), ("part_o", ctypes.c_void_p), ("part_m", ctypes.c_void_p),
+                ("part_e", ctypes.c_void_p)]
 
 
 class DistAttnError(RuntimeError):
@@ -72,6 +77,7 @@ def lib():
         L.da_combine.argtypes = [vp] * 7
         L.da_attention.argtypes = [vp] * 9 + [ctypes.c_size_t, vp]
         L.da_probe_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, vp, vp]
+        L.da_combine_multi.argtypes = [vp, ctypes.c_int32, vp, vp, vp]
         L.da_append.argtypes = [ctypes.POINTER(DaProblem)] + [vp] * 8
         L.da_block_pool_create.argtypes = [ctypes.c_int32, ctypes.POINTER(vp)]
         L.da_block_pool_destroy.argtypes = [vp]
@@ -298,3 +304,17 @@ class BlockPool:
         assert row.dtype.itemsize == 4 and row.flags["C_CONTIGUOUS"]
         st = lib().da_block_pool_release(self._h, block_tokens, ctypes.c_void_p(row.ctypes.data), length)
         _check(st, "da_block_pool_release")
+
+
+def combine_multi(sets, out=None, lse=None, stream=None):
+    """da_combine_multi.  ``sets`` is a list of (plan, part_o, part_m, part_e), one per KV share."""
+    arr = (DaPartialSet * len(sets))()
+    for i, (plan, po, pm, pe) in enumerate(sets):
+        arr[i].plan, arr[i].part_o, arr[i].part_m, arr[i].part_e = plan._h, po.data_ptr(), pm.data_ptr(), pe.data_ptr()
+    plan0 = sets[0][0]
+    if out is None:
+        out = torch.empty(plan0._out_shape() + (plan0.problem.head_dim,), dtype=torch.float32, device=sets[0][1].device)
+        lse = torch.empty(plan0._out_shape(), dtype=torch.float32, device=sets[0][1].device)
+    st = lib().da_combine_multi(ctypes.cast(arr, ctypes.c_void_p), len(sets), _ptr(out), _ptr(lse), _stream_ptr(stream))
+    _check(st, "da_combine_multi")
+    return out, lse

@@ -105,11 +105,11 @@ def test_schedule_properties_on_the_five_workloads(name):
     assert s["num_partials"] == int(ns.sum()) * r["Hq"]
     assert s["num_items"] == sum(_items_per_request(p, int(n), s["kernel"]) for n in ns)
     per_split = _items_per_request(p, 1, s["kernel"])
-    assert s["workgroups"] % per_split == 0 and s["workgroups"] <= 512
+    assert s["workgroups"] % per_split == 0 and s["workgroups"] <= 256
     if name != "c1_tiny":
-        # every compute unit gets its two persistent workgroups ...
-        assert s["workgroups"] == 512
-        runs = 512 // per_split
+        # every compute unit gets its persistent workgroup ...
+        assert s["workgroups"] == 256
+        runs = 256 // per_split
         # ... requests are cut no more than the equal-cost runs need ...
         assert int(ns.sum()) <= r["B"] + runs - 1
         # ... every workgroup reads (nearly) the same number of tokens ...
@@ -141,6 +141,6 @@ def test_schedule_of_a_large_batch_is_cheap_and_balanced():
         s = da.plan_schedule(p, lens, num_cus=256)
     dt = (time.perf_counter() - t0) / 5
     assert dt < 0.02, dt   # a few hundred microseconds in practice
-    assert s["workgroups"] == 512
-    assert s["max_workgroup_tokens"] <= 1.03 * float(lens.sum()) / 64 + 64
-    assert sum(s["nsplits"]) <= 4096 + 63
+    assert s["workgroups"] == 256
+    assert s["max_workgroup_tokens"] <= 1.03 * float(lens.sum()) / 32 + 64
+    assert sum(s["nsplits"]) <= 4096 + 31

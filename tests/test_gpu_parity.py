@@ -199,7 +199,7 @@ def test_many_small_requests_share_workgroups():
 
 
 def test_more_head_groups_than_workgroup_slots():
-    # Hkv * head tiles = 1024 > 512 persistent slots: one run per (kv-head, head tile), requests never split
+    # Hkv * head tiles = 1024 > 256 persistent slots: one run per (kv-head, head tile), requests never split
     w = synth.make(custom([100, 37], Hq=128 * 64, Hkv=128, T=16), DEV)
     prob = da.make_problem(w["q"], w["k_pool"], w["block_table"], w["scale"])
     s = da.plan_schedule(prob, w["seq_lens_host"].tolist(), kernel=da.DA_KERNEL_VALU)

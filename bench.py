@@ -80,8 +80,8 @@ def cpu_baseline(w, host, budget_s, threads):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2_7b", help="c1_tiny c2_7b c3_70b c4_2m c5_mixed")
     ap.add_argument("--len-div", type=int, default=1, help="divide every length (debug only; result is not the named workload)")
     ap.add_argument("--blocks-per-split", type=int, default=0)

@@ -7,6 +7,8 @@
 // the sum runs over all of them.
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
+
 #include "kernel_params.h"
 
 namespace da {
@@ -30,15 +32,37 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const CombineP
     const int slice = blockIdx.x % SLICES;
     const int r = pair / p.Hq;
     const int h = pair % p.Hq;
+    // per-set split count and first partial row of request r (set 0 may carry them in the kernel arguments)
+    int ns_of[kMaxPartialSets];
+    int64_t base_of[kMaxPartialSets];
     int total = 0;
-    for (int s = 0; s < p.num_sets; ++s) total += p.set[s].nsplits[r];
+#pragma unroll
+    for (int s = 0; s < kMaxPartialSets; ++s) {
+        ns_of[s] = 0;
+        base_of[s] = 0;
+        if (s < p.num_sets) {
+            if (s == 0 && p.set[0].nsplits == nullptr) {
+                // read from the kernel-argument segment itself (CombineParams is the only argument)
+                typedef const char __attribute__((address_space(4))) * kernarg_ptr;
+                const kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+                ns_of[0] = ((const int32_t __attribute__((address_space(4))) *)(ka + offsetof(CombineParams, inline_nsplits)))[r];
+                base_of[0] = ((const int64_t __attribute__((address_space(4))) *)(ka + offsetof(CombineParams, inline_row_base)))[r];
+            } else {
+                ns_of[s] = p.set[s].nsplits[r];
+                base_of[s] = p.set[s].row_base[r];
+            }
+        }
+        total += ns_of[s];
+    }
     if (p.skip_single && p.num_sets == 1 && total == 1) return;
 
     // pass 1: m_g
     float mg = kNegInf;
-    for (int s = 0; s < p.num_sets; ++s) {
-        const int ns = p.set[s].nsplits[r];
-        const float *pm = p.set[s].part_m + p.set[s].row_base[r] + (int64_t)h * ns;
+#pragma unroll
+    for (int s = 0; s < kMaxPartialSets; ++s) {
+        if (s >= p.num_sets) break;
+        const int ns = ns_of[s];
+        const float *pm = p.set[s].part_m + base_of[s] + (int64_t)h * ns;
         for (int j = tid; j < ns; j += kCombineThreads) mg = fmaxf(mg, pm[j]);
     }
 #pragma unroll
@@ -53,9 +77,11 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const CombineP
     const int rw = tid / COLS4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float eg = 0.0f;
-    for (int s = 0; s < p.num_sets; ++s) {
-        const int ns = p.set[s].nsplits[r];
-        const int64_t row0 = p.set[s].row_base[r] + (int64_t)h * ns;
+#pragma unroll
+    for (int s = 0; s < kMaxPartialSets; ++s) {
+        if (s >= p.num_sets) break;
+        const int ns = ns_of[s];
+        const int64_t row0 = base_of[s] + (int64_t)h * ns;
         const float *pm = p.set[s].part_m + row0;
         const float *pe = p.set[s].part_e + row0;
         const float4 *po = (const float4 *)(p.set[s].part_o + row0 * kHeadDim) + slice * COLS4 + c4;

@@ -46,6 +46,8 @@ struct da_plan {
     da::Schedule sched;
     std::vector<int32_t> lens;  // host lengths the schedule was made from
     size_t cap_entries = 0, cap_ranges = 0;
+    bool inline_ok = false;            // the schedule is small enough to travel in the kernel arguments
+    mutable bool dev_current = false;  // the device tables hold the current schedule
     char *dev = nullptr;       // device tables (+ error flag at layout.err)
     char *stage[kRing] = {};   // pinned host staging
     hipEvent_t ev[kRing] = {};
@@ -85,6 +87,14 @@ da_status reserve_tables(da_plan *pl, hipStream_t stream)
     return ok ? DA_OK : DA_ERR_HIP;
 }
 
+// Small schedules travel in the kernel arguments; the device tables are then filled only if something
+// asks for them (da_combine_multi).
+bool fits_inline(const da_plan *pl)
+{
+    return pl->sched.entries.size() <= (size_t)da::kInlineEntries && pl->sched.ranges <= da::kInlineRuns &&
+           pl->problem.batch <= da::kInlineBatch;
+}
+
 da_status upload(da_plan *pl, hipStream_t stream)
 {
     da_status st = reserve_tables(pl, stream);
@@ -109,15 +119,39 @@ da_status upload(da_plan *pl, hipStream_t stream)
         return DA_ERR_HIP;
     if (hipEventRecord(pl->ev[slot], stream) != hipSuccess) return DA_ERR_HIP;
     pl->ev_pending[slot] = true;
+    pl->dev_current = true;
     return DA_OK;
+}
+
+// After a (re-)plan: upload now, or leave it to the kernel arguments.
+da_status publish(da_plan *pl, hipStream_t stream)
+{
+    pl->inline_ok = fits_inline(pl);
+    pl->dev_current = false;
+    if (pl->inline_ok && pl->dev) return DA_OK;  // (the first call still allocates, for the error flag)
+    return upload(pl, stream);
+}
+
+// Device tables on demand, for launches that cannot take them inline.
+da_status need_device_tables(const da_plan *pl, hipStream_t stream)
+{
+    if (pl->dev_current) return DA_OK;
+    return upload(const_cast<da_plan *>(pl), stream);
 }
 
 void fill_micro(const da_plan *pl, da::MicroParams &mp)
 {
     const da_problem &p = pl->problem;
     const TableLayout lay = layout_of(pl);
-    mp.entries = (const da::SplitEntry *)(pl->dev + lay.entries);
-    mp.range_start = (const int32_t *)(pl->dev + lay.range_start);
+    if (pl->inline_ok) {
+        mp.entries = nullptr;
+        mp.range_start = nullptr;
+        std::memcpy(mp.inline_entries, pl->sched.entries.data(), sizeof(da::SplitEntry) * pl->sched.entries.size());
+        std::memcpy(mp.inline_range_start, pl->sched.range_start.data(), sizeof(int32_t) * pl->sched.range_start.size());
+    } else {
+        mp.entries = (const da::SplitEntry *)(pl->dev + lay.entries);
+        mp.range_start = (const int32_t *)(pl->dev + lay.range_start);
+    }
     mp.err_flag = (int32_t *)(pl->dev + lay.err);
     mp.B = p.batch;
     mp.Hq = p.num_q_heads;
@@ -156,6 +190,15 @@ void fill_set(const da_plan *pl, const float *part_o, const float *part_m, const
     ps.part_e = part_e;
     ps.nsplits = (const int32_t *)(pl->dev + lay.nsplits);
     ps.row_base = (const int64_t *)(pl->dev + lay.row_base);
+}
+
+// Single-set aggregation of a small plan: its two tables travel in the kernel arguments.
+void fill_set_inline(const da_plan *pl, da::CombineParams &cp)
+{
+    cp.set[0].nsplits = nullptr;
+    cp.set[0].row_base = nullptr;
+    std::memcpy(cp.inline_nsplits, pl->sched.nsplits.data(), sizeof(int32_t) * pl->problem.batch);
+    std::memcpy(cp.inline_row_base, pl->sched.row_base.data(), sizeof(int64_t) * pl->problem.batch);
 }
 
 void fill_combine(const da_plan *pl, da::CombineParams &cp)
@@ -250,7 +293,7 @@ da_status da_plan_create(const da_problem *problem, const int32_t *seq_lens_host
     pl->lens.assign(seq_lens_host, seq_lens_host + problem->batch);
     bool ok = true;
     for (int i = 0; ok && i < kRing; ++i) ok = hipEventCreateWithFlags(&pl->ev[i], hipEventDisableTiming) == hipSuccess;
-    if (ok) ok = upload(pl, (hipStream_t)stream) == DA_OK;
+    if (ok) ok = publish(pl, (hipStream_t)stream) == DA_OK;
     if (!ok) {
         da_plan_destroy(pl);
         return DA_ERR_HIP;
@@ -267,7 +310,7 @@ da_status da_plan_update(da_plan *pl, const int32_t *seq_lens_host, void *stream
     if (st != DA_OK) return st;
     pl->sched = std::move(s);
     pl->lens.assign(seq_lens_host, seq_lens_host + pl->problem.batch);
-    return upload(pl, (hipStream_t)stream);
+    return publish(pl, (hipStream_t)stream);
 }
 
 da_status da_plan_destroy(da_plan *pl)
@@ -356,6 +399,7 @@ da_status da_combine(const da_plan *pl, const float *part_o, const float *part_m
     da::CombineParams cp = {};
     fill_combine(pl, cp);
     fill_set(pl, part_o, part_m, part_e, cp.set[0]);
+    if (pl->inline_ok) fill_set_inline(pl, cp);
     cp.num_sets = 1;
     cp.out = out;
     cp.lse = lse;
@@ -375,6 +419,7 @@ da_status da_combine_multi(const da_partial_set *sets, int32_t num_sets, float *
         // every share describes the same queries: same batch, heads and query tokens
         if (a.batch != b.batch || a.num_q_heads != b.num_q_heads || (a.q_len > 0 ? a.q_len : 1) != (b.q_len > 0 ? b.q_len : 1))
             return DA_ERR_INVALID_ARG;
+        if (need_device_tables(s.plan, (hipStream_t)stream) != DA_OK) return DA_ERR_HIP;
         fill_set(s.plan, s.part_o, s.part_m, s.part_e, cp.set[i]);
     }
     fill_combine(sets[0].plan, cp);
@@ -420,6 +465,7 @@ da_status da_attention(const da_plan *pl, const void *q, const void *k_pool, con
     da::CombineParams cp = {};
     fill_combine(pl, cp);
     fill_set(pl, part_o, part_m, part_e, cp.set[0]);
+    if (pl->inline_ok) fill_set_inline(pl, cp);
     cp.num_sets = 1;
     cp.out = out;
     cp.lse = lse;

@@ -6,6 +6,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
+
 #include "kernel_params.h"
 
 namespace da {
@@ -92,7 +94,12 @@ __device__ __forceinline__ ItemInfo decode_item(const MicroParams &p, int e, int
     it.row_base = 0;
     if (!it.valid) return it;
     typedef const SplitEntry __attribute__((address_space(4))) * entry_ptr;
-    const entry_ptr ent = (entry_ptr)(uintptr_t)(p.entries + e);
+    // inline tables are read where the launch put them, in the kernel-argument segment (MicroParams is
+    // the kernels' only argument), never through `p` itself, which would drag the whole struct onto the stack
+    typedef const char __attribute__((address_space(4))) * kernarg_ptr;
+    const kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+    const entry_ptr ent = p.entries ? (entry_ptr)(uintptr_t)(p.entries + e)
+                                    : (entry_ptr)(ka + offsetof(MicroParams, inline_entries) + (size_t)e * sizeof(SplitEntry));
     it.r = ent->r;
     it.j = ent->j;
     it.ns = ent->ns;
@@ -172,3 +179,20 @@ __device__ __forceinline__ Chunk next_chunk(const MicroParams &p, const ItemInfo
 
 }  // namespace da
 
+
+namespace da {
+// First and one-past-last split of run `run`.
+__device__ __forceinline__ void run_bounds(const MicroParams &p, int run, int &e_begin, int &e_end)
+{
+    if (p.range_start) {
+        e_begin = table_load(p.range_start, run);
+        e_end = table_load(p.range_start, run + 1);
+    } else {
+        typedef const int32_t __attribute__((address_space(4))) * int_ptr;
+        typedef const char __attribute__((address_space(4))) * kernarg_ptr;
+        const int_ptr rs = (int_ptr)((kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr() + offsetof(MicroParams, inline_range_start));
+        e_begin = rs[run];
+        e_end = rs[run + 1];
+    }
+}
+}  // namespace da

@@ -17,6 +17,12 @@ struct SplitEntry {
     int64_t row_base;  // first partial row of the request
 };
 
+// Small schedules travel inside the kernel arguments instead of through device tables, which saves
+// the table upload (a copy engine round trip on the stream) on every re-plan.
+constexpr int kInlineEntries = 96;
+constexpr int kInlineRuns = 64;
+constexpr int kInlineBatch = 64;
+
 // One MicroAttention launch.  A work item is a (split, kv-head, head tile): the split's tokens are
 // read once and serve the head tile's q-heads.  The launch is persistent: workgroup b reads, for
 // (kv-head, head tile) number b % per_split, the splits entries[range_start[m] .. range_start[m+1])
@@ -32,8 +38,8 @@ struct MicroParams {
     float *part_e;
     float *out;  // used only for requests with one split when direct_out != 0
     float *lse;  // may be null
-    const SplitEntry *entries;   // every split of every request, in reading order
-    const int32_t *range_start;  // [ranges + 1]
+    const SplitEntry *entries;   // every split of every request, in reading order; null: inline_entries
+    const int32_t *range_start;  // [ranges + 1]; null: inline_range_start
     int32_t *err_flag;
     int32_t B, Hq, Hkv, G, T, max_blocks, num_phys;
     int32_t head_tile;          // columns served per work item
@@ -45,6 +51,8 @@ struct MicroParams {
     int32_t cols;               // (query token, q-head) columns per kv-head: q_len * G
     int64_t stride_block, stride_head, stride_token;  // elements
     float scale_log2e;          // scale * log2(e): scores are kept in base-2 units inside the kernels
+    int32_t inline_range_start[kInlineRuns + 1];
+    SplitEntry inline_entries[kInlineEntries];
 };
 
 constexpr int kMaxPartialSets = 4;
@@ -54,7 +62,7 @@ struct PartialSet {
     const float *part_o;
     const float *part_m;
     const float *part_e;
-    const int32_t *nsplits;   // [B] of the plan that made them
+    const int32_t *nsplits;   // [B] of the plan that made them; null (set 0 only): CombineParams::inline_*
     const int64_t *row_base;  // [B]
 };
 
@@ -66,6 +74,8 @@ struct CombineParams {
     int32_t B, Hq;  // Hq counts virtual heads (q_len * num_q_heads)
     int32_t skip_single;  // requests with one split were already normalised by the MicroAttention kernel
     int32_t col_slices;   // workgroups per (request, q-head), each owning 128 / col_slices columns
+    int32_t inline_nsplits[kInlineBatch];
+    int64_t inline_row_base[kInlineBatch];
 };
 
 }  // namespace da

@@ -130,8 +130,8 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
     const int combo = blockIdx.x - run * p.per_split;
     const int kvh = combo / p.head_tiles;
     const int ht = combo - kvh * p.head_tiles;
-    const int e_begin = table_load(p.range_start, run);
-    const int e_end = table_load(p.range_start, run + 1);
+    int e_begin, e_end;
+    run_bounds(p, run, e_begin, e_end);
     int round = 0;
     ItemInfo it = decode_item<kChunk>(p, e_begin, e_end, kvh, ht);
     Chunk cur = first_chunk<kChunk>(p, it, wave, lane);

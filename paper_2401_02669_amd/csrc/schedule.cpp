@@ -17,7 +17,7 @@ namespace da {
 
 namespace {
 constexpr int kGroupsPerCu = 1;          // persistent MicroAttention workgroups per compute unit (measured: 2 is 1-2 % slower)
-constexpr double kPartialBudget = 0.01;  // partial write + read traffic allowed, relative to KV bytes
+constexpr int64_t kMinRunTiles = 8;      // shortest run worth a workgroup: two tiles per wavefront
 constexpr int64_t kSplitCostTiles = 4;   // fixed cost of one split (look-up, merge, partial rows), in tiles
 }
 
@@ -113,13 +113,11 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
         for (int r = 0; r < B; ++r)
             for (int64_t t = f; t < s.ntiles[r]; t += f) cuts[r].push_back((int32_t)t);
     } else {
-        // a run must be worth its partial rows (written once, read once) and give every wavefront a tile
-        const double esize = p.kv_dtype == DA_BF16 ? 2.0 : 4.0;
-        const int heads_per_item = std::min(G, s.head_tile);
-        const double partial_bytes = 2.0 * heads_per_item * (p.head_dim + 2) * 4.0;
-        const double tile_bytes = 2.0 * p.head_dim * esize * kTileTokens;
-        const int64_t t_min = std::max<int64_t>(s.waves, (int64_t)std::ceil(partial_bytes / (kPartialBudget * tile_bytes)));
-        ranges = std::max<int64_t>(1, std::min<int64_t>(ranges, total_tiles / t_min));
+        // Big batches get one run per compute unit, and their partial rows are then a fraction of a
+        // percent of the KV bytes.  A small batch is latency-bound (one workgroup streams only a few
+        // tens of GB/s), so it is spread over as many compute units as have at least a few tiles to read,
+        // whatever that costs in partial rows.
+        ranges = std::max<int64_t>(1, std::min<int64_t>(ranges, total_tiles / kMinRunTiles));
         // equal-cost cut of the stream; a request costs its tiles plus a fixed amount per split
         const double total_cost = (double)total_tiles + (double)kSplitCostTiles * B;
         int64_t m = 1;          // next boundary to place

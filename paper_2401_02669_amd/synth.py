@@ -137,3 +137,71 @@ def f32_to_bf16_bits(x):
     """Round fp32 numpy values to bf16 (nearest-even, via torch) and return the uint16 bit patterns."""
     t = torch.as_tensor(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16)
     return t.view(torch.int16).numpy().view(np.uint16).copy()
+
+
+# ---- cluster states for the placement scheduler (Section 5.3) ---------------------------------------
+def natn_time_table(max_batch, weight_bytes=403e6, flops_per_token=0.403e9, hbm_bytes_per_s=7.0e12,
+                    flops_per_s=1.2e15, fixed_s=20e-6):
+    """Synthetic stand-in for the measured non-attention time of one layer at batch sizes 0..max_batch.
+
+    A two-regime curve: the layer's weights are read once per step whatever the batch, and the arithmetic grows with
+    the batch.  Defaults are a 4096-wide layer (12 h^2 parameters in bf16).  Entry 0 is 0 (an idle instance).
+    """
+    t = [0.0]
+    for b in range(1, max_batch + 1):
+        t.append(fixed_s + max(weight_bytes / hbm_bytes_per_s, b * flops_per_token / flops_per_s))
+    return t
+
+
+def attention_rate(kv_heads=32, head_dim=128, kv_elem_bytes=2, kv_read_bytes_per_s=7.0e12):
+    """g of Section 5.3 in tokens per second for one layer, from a measured KV-read rate of the MicroAttention kernel."""
+    return kv_read_bytes_per_s / (2 * kv_heads * head_dim * kv_elem_bytes)
+
+
+def make_cluster(seed, num_instances=32, block_tokens=256, capacity_blocks=2048, max_batch=256):
+    """Seeded cluster state: a mix of long-request, short-request, idle and middling instances.
+
+    Returns ``(model, instances)`` as plain dicts / lists of Python numbers:
+    model = {num_layers, block_tokens, attn_tokens_per_s, t_natn}; an instance = {req_tokens, req_remote_blocks,
+    hosted_blocks, capacity_blocks, waiting, admit_blocks}.  Lengths follow the ranges of Table 1 (a few tokens up to
+    2000K; longer than one instance can hold means part of the request is already remote).
+    """
+    rng = np.random.default_rng(BASE_SEED + 7919 * (seed + 1))
+    model = dict(num_layers=32, block_tokens=block_tokens, attn_tokens_per_s=attention_rate(),
+                 t_natn=natn_time_table(max_batch))
+    cap_tokens = capacity_blocks * block_tokens
+    instances = []
+    for _ in range(num_instances):
+        kind = rng.choice(4, p=[0.3, 0.45, 0.1, 0.15])
+        cap = int(capacity_blocks * rng.choice([1.0, 1.0, 0.5]))
+        remote = None
+        hosted = 0
+        if kind == 0:      # one long request filling most of the memory, few short ones beside it
+            long_len = int(rng.uniform(0.6, 1.6) * cap * block_tokens)
+            lens = [long_len] + [int(x) for x in rng.integers(16, 2000, size=int(rng.integers(0, 4)))]
+            blocks = [-(-s // block_tokens) for s in lens]
+            over = max(0, sum(blocks) - cap)
+            remote = [over + int(rng.integers(0, 8)) if over else 0] + [0] * (len(lens) - 1)
+            waiting, admit = int(rng.integers(0, 64)), int(rng.integers(1, 9))
+        elif kind == 1:    # many short requests, memory to spare
+            lens = [int(x) for x in rng.integers(16, 4000, size=int(rng.integers(8, min(max_batch, 120))))]
+            waiting, admit = int(rng.integers(0, 4)), int(rng.integers(1, 9))
+            hosted = int(rng.integers(0, 2)) * int(rng.integers(0, cap // 8))
+        elif kind == 2:    # idle
+            lens, waiting, admit = [], 0, 0
+        else:              # a handful of medium requests
+            lens = [int(x) for x in np.exp(rng.uniform(np.log(1000), np.log(cap_tokens // 8), size=int(rng.integers(1, 12))))]
+            waiting, admit = int(rng.integers(0, 16)), int(rng.integers(1, 17))
+        used = sum(-(-s // block_tokens) for s in lens) - (sum(remote) if remote else 0) + hosted
+        if used > cap:     # keep the state consistent: never more than the capacity in use
+            hosted = max(0, hosted - (used - cap))
+            used = sum(-(-s // block_tokens) for s in lens) - (sum(remote) if remote else 0) + hosted
+            if used > cap:
+                lens = lens[:1]
+                remote = remote[:1] if remote else None
+                used = -(-lens[0] // block_tokens) - (remote[0] if remote else 0)
+                if used > cap:
+                    remote = [(remote[0] if remote else 0) + used - cap]
+        instances.append(dict(req_tokens=lens, req_remote_blocks=remote if remote else [0] * len(lens),
+                              hosted_blocks=hosted, capacity_blocks=cap, waiting=waiting, admit_blocks=admit))
+    return model, instances

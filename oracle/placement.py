@@ -69,6 +69,11 @@ def remote_blocks(inst):
     return sum(inst.req_remote_blocks)
 
 
+def remote_tokens(model, inst):
+    """K^d in tokens: remote blocks are full except a request's last block, which goes last."""
+    return sum(min(rb * model.T, s) for s, rb in zip(inst.req_tokens, inst.req_remote_blocks))
+
+
 def used_blocks(model, inst):
     own = sum(blocks_of(model, s) for s in inst.req_tokens) + inst.admitted * inst.admit_blocks
     return own - remote_blocks(inst) + inst.hosted_blocks
@@ -100,8 +105,9 @@ def debtor_tps(model, inst, k):
     if beta2 == 0:
         return 0.0
     tokens = own_tokens(model, inst) + a * inst.admit_blocks * model.T
-    k_d = (remote_blocks(inst) + k) * model.T
-    t = layer_time(model, beta2, tokens) - k_d / model.g
+    k_d = remote_tokens(model, inst) + k * model.T
+    k_c = inst.hosted_blocks * model.T  # zero for an instance in the debtor role; kept so that k = 0 is the present state
+    t = layer_time(model, beta2, tokens) - k_d / model.g + k_c / model.g
     return beta2 / (model.n * t)
 
 
@@ -110,7 +116,7 @@ def creditor_tps(model, inst, k):
     beta = batch(inst)
     if beta == 0:
         return 0.0
-    k_own_remote = remote_blocks(inst) * model.T
+    k_own_remote = remote_tokens(model, inst)
     k_c = (inst.hosted_blocks + k) * model.T
     t = layer_time(model, beta, own_tokens(model, inst)) - k_own_remote / model.g + k_c / model.g
     return beta / (model.n * t)
@@ -121,7 +127,7 @@ def instance_tps(model, inst):
     beta = batch(inst)
     if beta == 0:
         return 0.0
-    t = layer_time(model, beta, own_tokens(model, inst)) - remote_blocks(inst) * model.T / model.g \
+    t = layer_time(model, beta, own_tokens(model, inst)) - remote_tokens(model, inst) / model.g \
         + inst.hosted_blocks * model.T / model.g
     return beta / (model.n * t)
 

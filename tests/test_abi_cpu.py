@@ -26,10 +26,14 @@ def problem(B=2, Hq=8, Hkv=2, d=128, T=256, max_blocks=64, num_phys=256, kv=da.D
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "distattn.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(da_[a-z_]+)\s*\(", header))
-    assert declared == set(da.EXPORTS), declared ^ set(da.EXPORTS)
+    from paper_2401_02669_amd import placement
+    declared = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        header = open(os.path.join(ROOT, "include", name)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared |= set(re.findall(r"\b(da_[a-z_]+)\s*\(", header))
+    exports = set(da.EXPORTS) | set(placement.EXPORTS)
+    assert declared == exports, declared ^ exports
     L = da.lib()
     for name in declared:
         assert hasattr(L, name), name

@@ -69,6 +69,22 @@ def test_existing_remote_blocks_shorten_the_debtor():
     assert P.instance_tps(m, d) == pytest.approx(1 / (10 * 0.004), rel=1e-14)
 
 
+def test_estimates_at_zero_blocks_are_the_present_state_whatever_the_role():
+    m = model([0.0, 0.001, 0.002])
+    i = P.Instance([1000, 3000], capacity_blocks=100, req_remote_blocks=[0, 10], hosted_blocks=7)
+    # T = 0.002 + 4000/1e6 - 1000/1e6 + 700/1e6 = 0.0057
+    assert P.instance_tps(m, i) == pytest.approx(2 / (10 * 0.0057), rel=1e-14)
+    assert P.debtor_tps(m, i, 0) == P.instance_tps(m, i)
+    assert P.creditor_tps(m, i, 0) == P.instance_tps(m, i)
+
+
+def test_a_remote_last_block_counts_its_tokens_only():
+    m = model([0.0, 0.001])
+    d = P.Instance([250], capacity_blocks=30, req_remote_blocks=[3])     # 3 blocks of 100: the last holds 50
+    assert P.remote_tokens(m, d) == 250
+    assert P.instance_tps(m, d) == pytest.approx(1 / (10 * 0.001), rel=1e-14)
+
+
 # ---- closed forms for the greedy choice --------------------------------------------------------------
 def test_idle_creditor_takes_all_but_the_last_block():
     # with beta_c = 0 the creditor loses nothing and the debtor's time falls with every block: best k = Block_max - 1

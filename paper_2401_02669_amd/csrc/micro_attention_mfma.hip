@@ -18,7 +18,7 @@
 //
 // The columns of a work item are (query token, q-head) pairs of the kv-head's group: q-heads for
 // plain decode, query tokens x q-heads in the multi-query form, where each column also has its own
-// causal limit.  A work item serves TILES (1 or 2) tiles of 16 columns from one K/V read.  Columns
+// causal limit.  A work item serves TILES (1, 2 or 4) tiles of 16 columns from one K/V read.  Columns
 // past the group carry q = 0 and are never written.
 #include <hip/hip_runtime.h>
 
@@ -324,6 +324,8 @@ hipError_t launch_micro_attention_mfma(const MicroParams &p, int grid, hipStream
         hipLaunchKernelGGL(micro_attention_mfma_kernel<1>, dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     else if (p.head_tile == 2 * kHeadTile)
         hipLaunchKernelGGL(micro_attention_mfma_kernel<2>, dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+    else if (p.head_tile == 4 * kHeadTile)
+        hipLaunchKernelGGL(micro_attention_mfma_kernel<4>, dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

@@ -81,7 +81,7 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
     s.kernel = kernel;
     s.waves = 4;
     if (kernel == DA_KERNEL_MFMA) {
-        s.head_tile = G > 16 ? 32 : 16;  // one or two 16-column matrix-core tiles per K/V read
+        s.head_tile = G > 32 ? 64 : G > 16 ? 32 : 16;  // one, two or four 16-column matrix-core tiles per K/V read
     } else {
         s.head_tile = 1;
         while (s.head_tile < G && s.head_tile < 8) s.head_tile *= 2;

@@ -109,7 +109,7 @@ def test_edge_lengths(dtype, kernel):
         assert_parity(out, lse, ref_out, ref_lse, dtype, "edge bps=%d" % bps)
 
 
-@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 8, 16])
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 8, 16, 24, 32, 64])
 @pytest.mark.parametrize("kernel", [da.DA_KERNEL_AUTO, da.DA_KERNEL_VALU], ids=["auto", "valu"])
 def test_group_sizes(G, kernel):
     w = synth.make(custom([700, 129, 2048], Hq=2 * G, Hkv=2, T=128), DEV)

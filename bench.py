@@ -227,6 +227,14 @@ def main():
     t_both = timed(lambda: (tmp.copy_(lens_m1), da.append(prob, k_new, v_new, w["k_pool"], w["v_pool"], w["block_table"], tmp)))
     assert torch.equal(tmp, w["seq_lens"])
     result["append_us"] = round(max(t_both - t_reset, 0.0) * 1e3, 2)
+    # the other rows of the path, each alone: host time of a re-plan (no stream work for small schedules) and
+    # the aggregation launch back to back (its stream time includes the launch floor of a few microseconds)
+    h0 = time.perf_counter()
+    for _ in range(200):
+        plan.update_raw(lens_c, sptr)
+    torch.cuda.synchronize()
+    result["plan_update_host_us"] = round((time.perf_counter() - h0) / 200 * 1e6, 2)
+    result["combine_us"] = round(timed(lambda: plan.combine(part_o, part_m, part_e, out, lse)) * 1e3, 2)
     plan.close()
     print(json.dumps(result), flush=True)
 

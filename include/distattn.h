@@ -81,7 +81,7 @@ typedef enum { DA_F32 = 0, DA_BF16 = 1 } da_dtype;
 
 /* MicroAttention kernel families (da_tuning.kernel). */
 typedef enum {
-    DA_KERNEL_AUTO = 0, /* VALU for group size 1 and for fp32 K/V, MFMA otherwise */
+    DA_KERNEL_AUTO = 0, /* MFMA when q, K and V are bf16, VALU otherwise (fp32 K/V or fp32 q) */
     DA_KERNEL_VALU = 1, /* fp32 vector ALU dot products, wavefront (DPP) reductions */
     DA_KERNEL_MFMA = 2  /* bf16 matrix-core products for the (q-head group) x (KV tile) contractions */
 } da_kernel;

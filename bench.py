@@ -201,7 +201,9 @@ def main():
             den = np.linalg.norm(ref)
             result["parity_on_sample"] = {
                 "max_abs": float(np.abs(got - ref).max()), "rel_l2": float(np.linalg.norm(got - ref) / den),
-                "fused_max_abs": float(np.abs(got2 - ref).max()), "pairs": int(len(pairs))}
+                "fused_max_abs": float(np.abs(got2 - ref).max()), "pairs": int(len(pairs)),
+                # worst single (request, q-head) pair, so that short requests are not hidden by long ones
+                "worst_pair_rel_l2": float(np.max(np.linalg.norm(got - ref, axis=-1) / np.maximum(np.linalg.norm(ref, axis=-1), 1e-300)))}
     # KV append (the step before attention in a decode iteration), timed apart from the attention step:
     # the last token of every request is rewritten in place, so the cache contents are left as they were
     k_new = torch.stack([w["k_pool"][int(w["block_table_host"][r, (L - 1) // w["T"]]), :, (L - 1) % w["T"]]
@@ -235,6 +237,27 @@ def main():
     torch.cuda.synchronize()
     result["plan_update_host_us"] = round((time.perf_counter() - h0) / 200 * 1e6, 2)
     result["combine_us"] = round(timed(lambda: plan.combine(part_o, part_m, part_e, out, lse)) * 1e3, 2)
+    h0 = time.perf_counter()
+    for _ in range(20):
+        da.Plan(prob, lens_list, blocks_per_split=args.blocks_per_split, kernel=args.kernel).close()
+    torch.cuda.synchronize()
+    result["plan_create_host_us"] = round((time.perf_counter() - h0) / 20 * 1e6, 1)
+    # what a pure streaming read of the same K pool sustains on this GPU right now (non-temporal loads, no
+    # arithmetic): the practical ceiling next to the 8 TB/s peak.  Skipped for cache-sized pools.
+    pool_bytes = w["k_pool"].numel() * w["k_pool"].element_size()
+    if pool_bytes >= (1 << 30):
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        best = 0.0
+        for variant in (3, 4):
+            for seg in (256 << 10, 1 << 20):
+                for wgs in (256, 512):
+                    t_probe = timed(lambda: da.probe_read(w["k_pool"], seg, wgs, variant, sink), reps=5)
+                    best = max(best, pool_bytes / (t_probe * 1e-3) / 1e9)
+        result["read_ceiling"] = {"GBps": round(best, 1), "probe": "da_probe_read over k_pool, best of 8 launch shapes",
+                                  "value_frac": round(value / best, 4), "kernel_frac": round(achieved / best, 4)}
+    props = torch.cuda.get_device_properties(0)
+    result["device"] = {"name": props.name, "compute_units": props.multi_processor_count,
+                        "hbm_GiB": round(props.total_memory / 2 ** 30, 1), "arch": getattr(props, "gcnArchName", "")}
     plan.close()
     print(json.dumps(result), flush=True)
 

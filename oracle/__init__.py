@@ -12,6 +12,7 @@ raw bit patterns.  Pools are addressed as
   micro_attention()  Section 4, m_j / e_j equation and Eq. 2
   aggregate()        Section 4, m_g / e_g equation and Eq. 3
   append()           Section 4: a new token's K/V rows join the block layout
+  move_blocks()      Section 5.3, move_kvcache of Algorithm 1: whole KV blocks go from one pool to another
 """
 import ctypes
 import os
@@ -68,6 +69,8 @@ def _load():
                                           ctypes.c_void_p, ctypes.c_void_p]
         _lib.oracle_append.restype = ctypes.c_int
         _lib.oracle_append.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int] * 7 + [ctypes.c_int64] * 3
+        _lib.oracle_move_blocks.restype = ctypes.c_int
+        _lib.oracle_move_blocks.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int] * 7 + [ctypes.c_int64] * 6
     return _lib
 
 
@@ -197,3 +200,25 @@ def append(k_new, v_new, k_pool, v_pool, block_table, seq_lens):
                                k_pool.itemsize, Hkv * T * d, T * d, d)
     if rc != 0:
         raise ValueError("oracle_append rejected its arguments")
+
+
+def move_blocks(k_src, v_src, k_dst, v_dst, src_ids, dst_ids):
+    """Copies blocks src_ids[i] of the source pools to blocks dst_ids[i] of the (writable) destination pools.
+
+    Pools are contiguous numpy arrays [P][Hkv][T][d] of one dtype; ids are int32 arrays of equal length; a pair
+    with an id outside its pool is skipped."""
+    Ps, Hkv, T, d = k_src.shape
+    Pd = k_dst.shape[0]
+    assert k_dst.shape[1:] == (Hkv, T, d) and v_src.shape == k_src.shape and v_dst.shape == k_dst.shape
+    assert k_src.dtype == v_src.dtype == k_dst.dtype == v_dst.dtype
+    for a in (k_src, v_src, k_dst, v_dst):
+        assert a.flags["C_CONTIGUOUS"]
+    assert k_dst.flags["WRITEABLE"] and v_dst.flags["WRITEABLE"]
+    src_ids = np.ascontiguousarray(src_ids, dtype=np.int32)
+    dst_ids = np.ascontiguousarray(dst_ids, dtype=np.int32)
+    assert src_ids.shape == dst_ids.shape and src_ids.ndim == 1
+    rc = _load().oracle_move_blocks(k_src.ctypes.data, v_src.ctypes.data, k_dst.ctypes.data, v_dst.ctypes.data,
+                                    src_ids.ctypes.data, dst_ids.ctypes.data, len(src_ids), Hkv, d, T, k_src.itemsize,
+                                    Ps, Pd, Hkv * T * d, T * d, d, Hkv * T * d, T * d, d)
+    if rc != 0:
+        raise ValueError("oracle_move_blocks rejected its arguments")

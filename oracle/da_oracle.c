@@ -300,3 +300,35 @@ int oracle_append(const void *k_new, const void *v_new, void *k_pool, void *v_po
     }
     return 0;
 }
+
+/*
+ * KV block movement (Section 5.3, move_kvcache of Algorithm 1; Section 5.2: part
+ * of a debtor's KV cache is placed in a creditor's memory).  Block src_ids[i] of
+ * the source pools is copied to block dst_ids[i] of the destination pools, all
+ * kv-heads, all T slots, K and V, bytes unchanged.  A pair with an id outside
+ * its pool is skipped.  Pairs are taken in order (a later pair may overwrite an
+ * earlier destination).  Pools are [P][Hkv][T][d] with the given element strides.
+ */
+int oracle_move_blocks(const void *k_src, const void *v_src, void *k_dst, void *v_dst,
+                       const int32_t *src_ids, const int32_t *dst_ids, int n,
+                       int Hkv, int d, int T, int elem_size, int num_src, int num_dst,
+                       int64_t src_stride_block, int64_t src_stride_head, int64_t src_stride_token,
+                       int64_t dst_stride_block, int64_t dst_stride_head, int64_t dst_stride_token)
+{
+    if (!k_src || !v_src || !k_dst || !v_dst || (n > 0 && (!src_ids || !dst_ids)))
+        return 1;
+    for (int i = 0; i < n; ++i) {
+        int64_t a = src_ids[i], b = dst_ids[i];
+        if (a < 0 || a >= num_src || b < 0 || b >= num_dst)
+            continue;
+        for (int g = 0; g < Hkv; ++g) {
+            for (int s = 0; s < T; ++s) {
+                int64_t from = (a * src_stride_block + g * src_stride_head + s * src_stride_token) * elem_size;
+                int64_t to = (b * dst_stride_block + g * dst_stride_head + s * dst_stride_token) * elem_size;
+                memcpy((char *)k_dst + to, (const char *)k_src + from, (size_t)d * elem_size);
+                memcpy((char *)v_dst + to, (const char *)v_src + from, (size_t)d * elem_size);
+            }
+        }
+    }
+    return 0;
+}

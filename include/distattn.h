@@ -245,6 +245,24 @@ da_status da_append(const da_problem *problem, const void *k_new, const void *v_
                     const int32_t *block_table, int32_t *seq_lens, int32_t *err_flags, void *stream);
 
 /*
+ * KV block movement (Section 5.3, move_kvcache of Algorithm 1; Section 5.2: a
+ * debtor places part of a request's KV cache in a creditor's memory): block
+ * src_ids[i] of (k_src, v_src) is copied to block dst_ids[i] of (k_dst, v_dst),
+ * all kv-heads and all block_tokens slots, bytes unchanged, for i <
+ * num_blocks.  src_ids / dst_ids are DEVICE int32 arrays.  The two layouts
+ * must agree in num_kv_heads, head_dim, block_tokens and kv_dtype; their
+ * strides and pool sizes may differ (fields used: those, num_phys_blocks and
+ * the three strides).  The destination ids must be distinct, and when source
+ * and destination are the same pools no destination block may also be a
+ * source.  A pair with an id outside its pool is skipped and bit 0 is OR-ed
+ * into *err_flags (device int32, may be NULL).  The caller rewrites the block
+ * tables; enqueue on a second stream to run the copy beside attention.
+ */
+da_status da_move_blocks(const da_problem *src_layout, const da_problem *dst_layout, const void *k_src,
+                         const void *v_src, void *k_dst, void *v_dst, const int32_t *src_ids, const int32_t *dst_ids,
+                         int32_t num_blocks, int32_t *err_flags, void *stream);
+
+/*
  * Host-side free list of physical KV blocks (Section 4: sub-blocks are the
  * unit in which the growing cache is managed; Section 5.1: they are pooled).
  * No GPU call.  da_block_pool_grow appends fresh block ids to a request's HOST

@@ -21,7 +21,7 @@ EXPORTS = [
     "da_plan_num_partials", "da_plan_split", "da_plan_nsplits", "da_workspace_bytes", "da_plan_error",
     "da_partial", "da_combine", "da_combine_multi", "da_attention", "da_probe_read", "da_append",
     "da_block_pool_create", "da_block_pool_destroy", "da_block_pool_free_count", "da_block_pool_grow",
-    "da_block_pool_release",
+    "da_block_pool_release", "da_move_blocks",
 ]
 
 
@@ -79,6 +79,7 @@ def lib():
         L.da_probe_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, vp, vp]
         L.da_combine_multi.argtypes = [vp, ctypes.c_int32, vp, vp, vp]
         L.da_append.argtypes = [ctypes.POINTER(DaProblem)] + [vp] * 8
+        L.da_move_blocks.argtypes = [ctypes.POINTER(DaProblem)] * 2 + [vp] * 6 + [ctypes.c_int32, vp, vp]
         L.da_block_pool_create.argtypes = [ctypes.c_int32, ctypes.POINTER(vp)]
         L.da_block_pool_destroy.argtypes = [vp]
         L.da_block_pool_free_count.argtypes = [vp, i32p]
@@ -269,6 +270,16 @@ def append(problem, k_new, v_new, k_pool, v_pool, block_table, seq_lens, err_fla
     st = lib().da_append(ctypes.byref(problem), _ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
                          _ptr(seq_lens), _ptr(err_flags), _stream_ptr(stream))
     _check(st, "da_append")
+
+
+def move_blocks(src_layout, dst_layout, k_src, v_src, k_dst, v_dst, src_ids, dst_ids, err_flags=None, stream=None):
+    """Enqueue da_move_blocks: blocks src_ids[i] of the source pools are copied to blocks dst_ids[i] of the
+    destination pools (device int32 id tensors of equal length)."""
+    assert src_ids.dtype == torch.int32 and dst_ids.dtype == torch.int32 and src_ids.numel() == dst_ids.numel()
+    st = lib().da_move_blocks(ctypes.byref(src_layout), ctypes.byref(dst_layout), _ptr(k_src), _ptr(v_src), _ptr(k_dst),
+                              _ptr(v_dst), _ptr(src_ids), _ptr(dst_ids), src_ids.numel(), _ptr(err_flags),
+                              _stream_ptr(stream))
+    _check(st, "da_move_blocks")
 
 
 class BlockPool:

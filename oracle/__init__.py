@@ -24,7 +24,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "da_oracle.c")
 _LIB = os.path.join(_HERE, "libda_oracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 
 
 def build(force=False):
@@ -79,7 +79,9 @@ def _dtype_code(a):
         return F32
     if a.dtype == np.uint16:
         return BF16
-    raise TypeError("oracle takes float32 or uint16 (bf16 bits), got %s" % a.dtype)
+    if a.dtype == np.float16:
+        return F16
+    raise TypeError("oracle takes float32, float16 or uint16 (bf16 bits), got %s" % a.dtype)
 
 
 def _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, strides, keep):
@@ -189,7 +191,7 @@ def append(k_new, v_new, k_pool, v_pool, block_table, seq_lens):
     B, Hkv, d = k_new.shape
     P, Hkv2, T, d2 = k_pool.shape
     assert (Hkv2, d2) == (Hkv, d) and v_pool.shape == k_pool.shape and v_new.shape == k_new.shape
-    assert k_pool.dtype == k_new.dtype == v_pool.dtype == v_new.dtype and _dtype_code(k_pool) in (F32, BF16)
+    assert k_pool.dtype == k_new.dtype == v_pool.dtype == v_new.dtype and _dtype_code(k_pool) in (F32, BF16, F16)
     for a in (k_pool, v_pool, seq_lens):
         assert a.flags["C_CONTIGUOUS"] and a.flags["WRITEABLE"]
     assert block_table.dtype == np.int32 and seq_lens.dtype == np.int32 and block_table.flags["C_CONTIGUOUS"]

@@ -6,7 +6,7 @@
  * path, and nothing in the product path may call it: only the tests, the smoke
  * check and the benchmark's cpu_baseline leg do.
  *
- * Everything is computed in fp64.  Stored inputs (fp32, or bf16 held as
+ * Everything is computed in fp64.  Stored inputs (fp32, IEEE half, or bf16 held as
  * uint16) are widened exactly; nothing is blocked, fused or reordered beyond
  * what the cited formula states.
  *
@@ -44,13 +44,26 @@
 #include <stdint.h>
 #include <string.h>
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 
 /* Exact widening of one stored element to fp64. */
 static double widen(const void *base, int dtype, int64_t idx)
 {
     if (dtype == ORACLE_F32)
         return (double)((const float *)base)[idx];
+    if (dtype == ORACLE_F16) {
+        /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
+        uint16_t h = ((const uint16_t *)base)[idx];
+        int sign = h >> 15, expo = (h >> 10) & 31, frac = h & 1023;
+        double v;
+        if (expo == 0)
+            v = ldexp((double)frac, -24);                 /* zero and subnormals: frac * 2^-24 */
+        else if (expo == 31)
+            v = frac ? NAN : INFINITY;
+        else
+            v = ldexp(1.0 + (double)frac / 1024.0, expo - 15);
+        return sign ? -v : v;
+    }
     /* bf16 is the upper half of an IEEE fp32 */
     uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
     float f;

@@ -19,6 +19,9 @@
  * All kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL =
  * the default stream); no entry point except da_plan_error synchronises.
  *
+ * Element types (da_dtype): fp32, bf16 and IEEE half for q and for the pools; the
+ * matrix-core kernel needs q and the pools in the same 16-bit type.
+ *
  * Layouts (element = one kv_dtype / q_dtype value; strides in elements):
  *   q            [batch][num_q_heads][head_dim], contiguous
  *   k_pool,v_pool element (pb, g, s, c) at pb*kv_block_stride + g*kv_head_stride
@@ -77,11 +80,11 @@ typedef enum {
     DA_ERR_NO_SPACE = 5     /* the block pool has too few free blocks */
 } da_status;
 
-typedef enum { DA_F32 = 0, DA_BF16 = 1 } da_dtype;
+typedef enum { DA_F32 = 0, DA_BF16 = 1, DA_F16 = 2 /* IEEE binary16 */ } da_dtype;
 
 /* MicroAttention kernel families (da_tuning.kernel). */
 typedef enum {
-    DA_KERNEL_AUTO = 0, /* MFMA when q, K and V are bf16, VALU otherwise (fp32 K/V or fp32 q) */
+    DA_KERNEL_AUTO = 0, /* MFMA when q, K and V share a 16-bit type (bf16 or half), VALU otherwise */
     DA_KERNEL_VALU = 1, /* fp32 vector ALU dot products, wavefront (DPP) reductions */
     DA_KERNEL_MFMA = 2  /* bf16 matrix-core products for the (q-head group) x (KV tile) contractions */
 } da_kernel;

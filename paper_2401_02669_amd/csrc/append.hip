@@ -74,8 +74,8 @@ extern "C" da_status da_append(const da_problem *problem, const void *k_new, con
     const da_problem &q = *problem;
     if (q.batch < 1 || q.num_kv_heads < 1 || q.block_tokens < 1 || q.max_blocks_per_seq < 1 || q.num_phys_blocks < 1)
         return DA_ERR_INVALID_ARG;
-    if (q.head_dim != 128 || (q.kv_dtype != DA_F32 && q.kv_dtype != DA_BF16)) return DA_ERR_UNSUPPORTED;
-    const int64_t esize = q.kv_dtype == DA_BF16 ? 2 : 4;
+    if (q.head_dim != 128 || (q.kv_dtype < DA_F32 || q.kv_dtype > DA_F16)) return DA_ERR_UNSUPPORTED;
+    const int64_t esize = q.kv_dtype == DA_F32 ? 4 : 2;
     if (q.kv_token_stride < q.head_dim || q.kv_head_stride < 0 || q.kv_block_stride < 0) return DA_ERR_INVALID_ARG;
     if ((q.kv_token_stride * esize) % 16 || (q.kv_head_stride * esize) % 16 || (q.kv_block_stride * esize) % 16)
         return DA_ERR_INVALID_ARG;

@@ -10,7 +10,7 @@
 #include "schedule.h"
 
 namespace da {
-hipError_t launch_micro_attention_valu(const MicroParams &p, bool kv_bf16, int grid, hipStream_t stream);
+hipError_t launch_micro_attention_valu(const MicroParams &p, int grid, hipStream_t stream);
 hipError_t launch_micro_attention_mfma(const MicroParams &p, int grid, hipStream_t stream);
 hipError_t launch_combine(const CombineParams &p, hipStream_t stream);
 }  // namespace da
@@ -165,7 +165,8 @@ void fill_micro(const da_plan *pl, da::MicroParams &mp)
     mp.per_split = p.num_kv_heads * pl->sched.head_tiles;
     mp.q_len = p.q_len > 0 ? p.q_len : 1;
     mp.cols = mp.q_len * mp.G;
-    mp.q_bf16 = p.q_dtype == DA_BF16;
+    mp.q_dtype = p.q_dtype;
+    mp.kv_dtype = p.kv_dtype;
     mp.stride_block = p.kv_block_stride;
     mp.stride_head = p.kv_head_stride;
     mp.stride_token = p.kv_token_stride;
@@ -176,7 +177,7 @@ da_status launch_micro(const da_plan *pl, const da::MicroParams &mp, hipStream_t
 {
     hipError_t e = hipErrorInvalidValue;
     if (pl->sched.kernel == DA_KERNEL_VALU)
-        e = da::launch_micro_attention_valu(mp, pl->problem.kv_dtype == DA_BF16, pl->sched.grid, stream);
+        e = da::launch_micro_attention_valu(mp, pl->sched.grid, stream);
     else if (pl->sched.kernel == DA_KERNEL_MFMA)
         e = da::launch_micro_attention_mfma(mp, pl->sched.grid, stream);
     return e == hipSuccess ? DA_OK : DA_ERR_HIP;

@@ -44,7 +44,8 @@ struct MicroParams {
     int32_t B, Hq, Hkv, G, T, max_blocks, num_phys;
     int32_t head_tile;          // columns served per work item
     int32_t head_tiles;         // ceil(cols / head_tile)
-    int32_t q_bf16;
+    int32_t q_dtype;            // da_dtype of q
+    int32_t kv_dtype;           // da_dtype of the pools
     int32_t direct_out;
     int32_t per_split;          // Hkv * head_tiles
     int32_t q_len;              // query tokens per request

@@ -1,4 +1,4 @@
-// MicroAttention on the matrix cores, for grouped-query attention with bf16 q / K / V
+// MicroAttention on the matrix cores, for q / K / V in one 16-bit type (bf16 or IEEE half), any group size
 // (Section 4, m_j / e_j equation and Eq. 2; Section 3: the q-heads of a GQA group share one K/V read).
 //
 // A work item is a run of tokens of one (request, kv-head) and a tile of up to 16 q-heads of its
@@ -7,7 +7,7 @@
 // item's partial result is merged and written, so the memory pipe never drains between items.
 // Each wavefront walks 32-token chunks on its own:
 //
-//   S  = K  . Q^T   v_mfma_f32_16x16x32_bf16, A = 16 token rows of K (16 B of a row per lane, loaded
+//   S  = K  . Q^T   v_mfma_f32_16x16x32_bf16 / _f16, A = 16 token rows of K (16 B of a row per lane, loaded
 //                   straight from HBM in operand layout), B = Q^T (head = lane % 16).  bf16 x bf16
 //                   products are exact and summed in fp32.
 //   P  = exp2(S * scale*log2e - m), running m / e per head (head = lane % 16 in every step).
@@ -22,6 +22,7 @@
 // past the group carry q = 0 and are never written.
 #include <hip/hip_runtime.h>
 
+#include "../../include/distattn.h"
 #include "item_walk.h"
 #include "kernel_params.h"
 
@@ -30,6 +31,8 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -54,12 +57,45 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 // displacing anything in the caches (measurably faster than a plain load on this GPU).
 __device__ __forceinline__ u32x4 load16_stream(const char *p) { return __builtin_nontemporal_load((const u32x4 *)p); }
 
-__device__ __forceinline__ f32x4 mfma_bf16(const u32x4 &a, const u32x4 &b, f32x4 c)
+// 16 x 16 x 32 matrix-core product of 16-bit operands with fp32 accumulation; F16: IEEE half, else bf16
+template <bool F16>
+__device__ __forceinline__ f32x4 mfma16(const u32x4 &a, const u32x4 &b, f32x4 c)
 {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-template <int TILES>
+// Softmax weights go into the PV product as a high + a low 16-bit part, so that they carry about 16 (bf16) or 22
+// (half) mantissa bits.  Half has a narrow exponent (numbers under 6.1e-5 lose mantissa bits, under 6e-8 they
+// vanish): the kernel hands over weights relative to the chunk's own maximum (largest = 1) multiplied by 2^15
+// (below the largest half, 65504), so that within a chunk weights down to 2^-29 of the largest keep their full
+// precision; the chunk's product is scaled back when it is added to the accumulator.
+template <bool F16>
+struct Weights;
+template <>
+struct Weights<false> {
+    static __device__ __forceinline__ void split(float a, float b, uint32_t &hi, uint32_t &lo)
+    {
+        hi = pack_bf16(a, b);
+        lo = pack_bf16(a - as_f(hi << 16), b - as_f(hi & 0xFFFF0000u));
+    }
+};
+template <>
+struct Weights<true> {
+    static constexpr float kScale = 32768.0f, kUnscale = 1.0f / 32768.0f;
+    static __device__ __forceinline__ void split(float a, float b, uint32_t &hi, uint32_t &lo)
+    {
+        a *= kScale;
+        b *= kScale;
+        const fp16x2 h = __builtin_amdgcn_cvt_pkrtz(a, b);  // toward zero: the remainder is >= 0 and exact in fp32
+        hi = __builtin_bit_cast(uint32_t, h);
+        lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a - (float)h[0], b - (float)h[1]));
+    }
+};
+
+template <int TILES, bool F16>
 __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const MicroParams p)
 {
     constexpr int COLS = kHeadTile * TILES;  // columns per work item
@@ -176,8 +212,8 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
             for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
                 for (int tl = 0; tl < TILES; ++tl) {
-                    s0[tl] = mfma_bf16(kr[ks], qreg[tl][ks], s0[tl]);
-                    s1[tl] = mfma_bf16(kr[4 + ks], qreg[tl][ks], s1[tl]);
+                    s0[tl] = mfma16<F16>(kr[ks], qreg[tl][ks], s0[tl]);
+                    s1[tl] = mfma16<F16>(kr[4 + ks], qreg[tl][ks], s1[tl]);
                 }
             }
             load_k(kf_next, kr);
@@ -186,7 +222,8 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
                 continue;
             }
 
-            u32x4 ph[TILES], pl[TILES];  // P^T operands: 8 tokens of this lane group, column ln; high and low bf16 parts
+            u32x4 ph[TILES], pl[TILES];  // P^T operands: 8 tokens of this lane group, column ln; high and low 16-bit parts
+            float beta[TILES];           // half only: what the chunk's product is multiplied by when it joins acc
 #pragma unroll
             for (int tl = 0; tl < TILES; ++tl) {
                 // scores in base-2 units (scale * log2(e) applied); rows past the valid or visible tokens masked out
@@ -206,45 +243,66 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
                 const float mu = (mn == kNegInf) ? 0.0f : mn;
                 const float alpha = fast_exp2(m[tl] - mu);
                 m[tl] = mn;
+                // bf16 has fp32's exponent range: weights are taken against the running maximum.  Half does not:
+                // weights are taken against the chunk's own maximum, so the largest is 1, and the chunk's product
+                // is rescaled by beta when it joins acc.
+                const float ref = F16 ? ((cm == kNegInf) ? 0.0f : cm) : mu;
                 float sum = 0.0f;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    s[i] = fast_exp2(s[i] - mu);
+                    s[i] = fast_exp2(s[i] - ref);
                     sum += s[i];
                 }
-                e[tl] = fmaf(e[tl], alpha, sum);
+                beta[tl] = F16 ? fast_exp2(ref - mu) : 1.0f;
+                e[tl] = fmaf(e[tl], alpha, F16 ? sum * beta[tl] : sum);
                 if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
                     for (int n = 0; n < 8; ++n) acc[tl][n] *= alpha;
                 }
                 uint32_t h[4], l[4];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    h[t] = pack_bf16(s[2 * t], s[2 * t + 1]);
-                    const float r0 = s[2 * t] - as_f(h[t] << 16);
-                    const float r1 = s[2 * t + 1] - as_f(h[t] & 0xFFFF0000u);
-                    l[t] = pack_bf16(r0, r1);
-                }
+                for (int t = 0; t < 4; ++t) Weights<F16>::split(s[2 * t], s[2 * t + 1], h[t], l[t]);
                 ph[tl] = u32x4{h[0], h[1], h[2], h[3]};
                 pl[tl] = u32x4{l[0], l[1], l[2], l[3]};
             }
 
             // O^T += V^T . P^T, 8 MFMA dimension groups; group n takes dims 8*m + n, m = MFMA row
+            u32x4 ve[4], vo[4];
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
                 const uint32_t d0 = vr[0][w], d1 = vr[1][w], d2 = vr[2][w], d3 = vr[3][w];
                 const uint32_t d4 = vr[4][w], d5 = vr[5][w], d6 = vr[6][w], d7 = vr[7][w];
                 // even dim 2w: low halves; odd dim 2w+1: high halves; (token 2t, token 2t+1) per register
-                const u32x4 ve = u32x4{__builtin_amdgcn_perm(d1, d0, 0x05040100u), __builtin_amdgcn_perm(d3, d2, 0x05040100u),
-                                       __builtin_amdgcn_perm(d5, d4, 0x05040100u), __builtin_amdgcn_perm(d7, d6, 0x05040100u)};
-                const u32x4 vo = u32x4{__builtin_amdgcn_perm(d1, d0, 0x07060302u), __builtin_amdgcn_perm(d3, d2, 0x07060302u),
-                                       __builtin_amdgcn_perm(d5, d4, 0x07060302u), __builtin_amdgcn_perm(d7, d6, 0x07060302u)};
+                ve[w] = u32x4{__builtin_amdgcn_perm(d1, d0, 0x05040100u), __builtin_amdgcn_perm(d3, d2, 0x05040100u),
+                              __builtin_amdgcn_perm(d5, d4, 0x05040100u), __builtin_amdgcn_perm(d7, d6, 0x05040100u)};
+                vo[w] = u32x4{__builtin_amdgcn_perm(d1, d0, 0x07060302u), __builtin_amdgcn_perm(d3, d2, 0x07060302u),
+                              __builtin_amdgcn_perm(d5, d4, 0x07060302u), __builtin_amdgcn_perm(d7, d6, 0x07060302u)};
+            }
+            if constexpr (F16) {
 #pragma unroll
                 for (int tl = 0; tl < TILES; ++tl) {
-                    acc[tl][2 * w] = mfma_bf16(ve, ph[tl], acc[tl][2 * w]);
-                    acc[tl][2 * w] = mfma_bf16(ve, pl[tl], acc[tl][2 * w]);
-                    acc[tl][2 * w + 1] = mfma_bf16(vo, ph[tl], acc[tl][2 * w + 1]);
-                    acc[tl][2 * w + 1] = mfma_bf16(vo, pl[tl], acc[tl][2 * w + 1]);
+                    f32x4 part[8];  // the chunk's own V^T . P^T, weights relative to the chunk maximum
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        part[2 * w] = mfma16<F16>(ve[w], ph[tl], f32x4{0.f, 0.f, 0.f, 0.f});
+                        part[2 * w] = mfma16<F16>(ve[w], pl[tl], part[2 * w]);
+                        part[2 * w + 1] = mfma16<F16>(vo[w], ph[tl], f32x4{0.f, 0.f, 0.f, 0.f});
+                        part[2 * w + 1] = mfma16<F16>(vo[w], pl[tl], part[2 * w + 1]);
+                    }
+                    const float b = beta[tl] * Weights<F16>::kUnscale;
+#pragma unroll
+                    for (int n = 0; n < 8; ++n) acc[tl][n] += part[n] * b;
+                }
+            } else {
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+#pragma unroll
+                    for (int tl = 0; tl < TILES; ++tl) {
+                        acc[tl][2 * w] = mfma16<F16>(ve[w], ph[tl], acc[tl][2 * w]);
+                        acc[tl][2 * w] = mfma16<F16>(ve[w], pl[tl], acc[tl][2 * w]);
+                        acc[tl][2 * w + 1] = mfma16<F16>(vo[w], ph[tl], acc[tl][2 * w + 1]);
+                        acc[tl][2 * w + 1] = mfma16<F16>(vo[w], pl[tl], acc[tl][2 * w + 1]);
+                    }
                 }
             }
             cur = nxt;
@@ -315,20 +373,29 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
     }
 }
 
-}  // namespace
-
-hipError_t launch_micro_attention_mfma(const MicroParams &p, int grid, hipStream_t stream)
+template <bool F16>
+hipError_t launch_tiles(const MicroParams &p, int grid, hipStream_t stream)
 {
-    if (!p.q_bf16 || grid < 1) return hipErrorInvalidValue;
     if (p.head_tile == kHeadTile)
-        hipLaunchKernelGGL(micro_attention_mfma_kernel<1>, dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+        hipLaunchKernelGGL((micro_attention_mfma_kernel<1, F16>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     else if (p.head_tile == 2 * kHeadTile)
-        hipLaunchKernelGGL(micro_attention_mfma_kernel<2>, dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+        hipLaunchKernelGGL((micro_attention_mfma_kernel<2, F16>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     else if (p.head_tile == 4 * kHeadTile)
-        hipLaunchKernelGGL(micro_attention_mfma_kernel<4>, dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+        hipLaunchKernelGGL((micro_attention_mfma_kernel<4, F16>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
+}
+
+}  // namespace
+
+// q, K and V share one 16-bit type (bf16 or IEEE half); head_tile is 16, 32 or 64.
+hipError_t launch_micro_attention_mfma(const MicroParams &p, int grid, hipStream_t stream)
+{
+    if (grid < 1 || p.q_dtype != p.kv_dtype) return hipErrorInvalidValue;
+    if (p.kv_dtype == DA_BF16) return launch_tiles<false>(p, grid, stream);
+    if (p.kv_dtype == DA_F16) return launch_tiles<true>(p, grid, stream);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace da

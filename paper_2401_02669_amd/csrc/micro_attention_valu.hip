@@ -10,6 +10,7 @@
 // (m, e, o) in base-2 units; they are merged once, at the end of the item.
 #include <hip/hip_runtime.h>
 
+#include "../../include/distattn.h"
 #include "item_walk.h"
 #include "kernel_params.h"
 
@@ -51,10 +52,31 @@ __device__ __forceinline__ float row32_sum(float x)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <bool BF16>
-struct Slice;  // a lane's 16 bytes of one token row
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+// two IEEE halves in one register -> two floats (exact, subnormals included)
+__device__ __forceinline__ void half2_to_float(uint32_t w, float &lo, float &hi)
+{
+    const f16x2 h = __builtin_bit_cast(f16x2, w);
+    lo = (float)h[0];
+    hi = (float)h[1];
+}
+
+template <int KV>
+struct Slice;  // a lane's 16 bytes of one token row; KV = da_dtype of the pools
 template <>
-struct Slice<true> {
+struct Slice<DA_F16> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void unpack(const u32x4 &r, float (&f)[8])
+    {
+        half2_to_float(r.x, f[0], f[1]);
+        half2_to_float(r.y, f[2], f[3]);
+        half2_to_float(r.z, f[4], f[5]);
+        half2_to_float(r.w, f[6], f[7]);
+    }
+};
+template <>
+struct Slice<DA_BF16> {
     static constexpr int N = 8;
     static __device__ __forceinline__ void unpack(const u32x4 &r, float (&f)[8])
     {
@@ -65,7 +87,7 @@ struct Slice<true> {
     }
 };
 template <>
-struct Slice<false> {
+struct Slice<DA_F32> {
     static constexpr int N = 4;
     static __device__ __forceinline__ void unpack(const u32x4 &r, float (&f)[4])
     {
@@ -77,15 +99,15 @@ constexpr float kNegInf = -__builtin_inff();
 constexpr float kLn2 = 0.69314718055994530942f;
 constexpr int kWaves = 4;  // wavefronts per workgroup
 
-// KVBF16: K/V storage is bf16 (else fp32).  GT: q-heads per item.  NL: load instructions per chunk.
-template <bool KVBF16, int GT, int NL>
+// KV: da_dtype of the K/V pools.  GT: q-heads per item.  NL: load instructions per chunk.
+template <int KV, int GT, int NL>
 __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const MicroParams p)
 {
-    constexpr int EPL = Slice<KVBF16>::N;  // elements per lane
-    constexpr int LPR = kHeadDim / EPL;    // lanes per token row: 16 (bf16) or 32 (fp32)
+    constexpr int EPL = Slice<KV>::N;  // elements per lane
+    constexpr int LPR = kHeadDim / EPL;    // lanes per token row: 16 (16-bit types) or 32 (fp32)
     constexpr int RPL = 64 / LPR;          // token rows per load instruction: 4 or 2
     constexpr int CH = NL * RPL;           // tokens per chunk (divides the 32-token tile)
-    constexpr int ESIZE = KVBF16 ? 2 : 4;
+    constexpr int ESIZE = KV == DA_F32 ? 4 : 2;
     static_assert(kTile % CH == 0, "a chunk must divide the scheduling tile");
 
     // cross-wavefront merge buffers, two sets used alternately by consecutive items
@@ -127,15 +149,19 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
             visible[g] = live ? col.visible : 0;
             const int64_t qoff = ((int64_t)it.r * p.q_len * p.Hq + col.vh) * kHeadDim + colc * EPL;
             float x[EPL];
-            if (p.q_bf16) {
+            if (p.q_dtype != DA_F32) {
                 uint32_t w[EPL / 2];
                 const uint32_t *src = (const uint32_t *)((const uint16_t *)p.q + qoff);
 #pragma unroll
                 for (int c = 0; c < EPL / 2; ++c) w[c] = src[c];
 #pragma unroll
                 for (int c = 0; c < EPL / 2; ++c) {
-                    x[2 * c] = as_f(w[c] << 16);
-                    x[2 * c + 1] = as_f(w[c] & 0xFFFF0000u);
+                    if (p.q_dtype == DA_BF16) {
+                        x[2 * c] = as_f(w[c] << 16);
+                        x[2 * c + 1] = as_f(w[c] & 0xFFFF0000u);
+                    } else {
+                        half2_to_float(w[c], x[2 * c], x[2 * c + 1]);
+                    }
                 }
             } else {
                 const float *src = (const float *)p.q + qoff;
@@ -195,7 +221,7 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
 #pragma unroll
             for (int jj = 0; jj < NL; ++jj) {
                 float kf[EPL];
-                Slice<KVBF16>::unpack(kr[jj], kf);
+                Slice<KV>::unpack(kr[jj], kf);
 #pragma unroll
                 for (int g = 0; g < GT; ++g) {
                     float acc = 0.0f;
@@ -231,7 +257,7 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
 #pragma unroll
                 for (int jj = 0; jj < NL; ++jj) {
                     float vf[EPL];
-                    Slice<KVBF16>::unpack(vr[jj], vf);
+                    Slice<KV>::unpack(vr[jj], vf);
 #pragma unroll
                     for (int g = 0; g < GT; ++g)
 #pragma unroll
@@ -310,24 +336,35 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_valu_kernel(const
     }
 }
 
-template <bool KVBF16, int GT, int NL>
+template <int KV, int GT, int NL>
 hipError_t launch_one(const MicroParams &p, int grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((micro_attention_valu_kernel<KVBF16, GT, NL>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+    hipLaunchKernelGGL((micro_attention_valu_kernel<KV, GT, NL>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     return hipGetLastError();
+}
+
+template <int KV>
+hipError_t launch_for(const MicroParams &p, int grid, hipStream_t stream)
+{
+    switch (p.head_tile) {
+    case 1: return launch_one<KV, 1, 8>(p, grid, stream);
+    case 2: return launch_one<KV, 2, 8>(p, grid, stream);
+    case 4: return launch_one<KV, 4, 4>(p, grid, stream);
+    case 8: return launch_one<KV, 8, 2>(p, grid, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
 
 // head_tile must be 1, 2, 4 or 8.
-hipError_t launch_micro_attention_valu(const MicroParams &p, bool kv_bf16, int grid, hipStream_t stream)
+hipError_t launch_micro_attention_valu(const MicroParams &p, int grid, hipStream_t stream)
 {
     if (grid < 1) return hipErrorInvalidValue;
-    switch (p.head_tile) {
-    case 1: return kv_bf16 ? launch_one<true, 1, 8>(p, grid, stream) : launch_one<false, 1, 8>(p, grid, stream);
-    case 2: return kv_bf16 ? launch_one<true, 2, 8>(p, grid, stream) : launch_one<false, 2, 8>(p, grid, stream);
-    case 4: return kv_bf16 ? launch_one<true, 4, 4>(p, grid, stream) : launch_one<false, 4, 4>(p, grid, stream);
-    case 8: return kv_bf16 ? launch_one<true, 8, 2>(p, grid, stream) : launch_one<false, 8, 2>(p, grid, stream);
+    switch (p.kv_dtype) {
+    case DA_F32: return launch_for<DA_F32>(p, grid, stream);
+    case DA_BF16: return launch_for<DA_BF16>(p, grid, stream);
+    case DA_F16: return launch_for<DA_F16>(p, grid, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -71,10 +71,10 @@ extern "C" da_status da_move_blocks(const da_problem *src_layout, const da_probl
     if (num_blocks > 0 && (!src_ids || !dst_ids)) return DA_ERR_INVALID_ARG;
     const da_problem &a = *src_layout, &b = *dst_layout;
     if (a.head_dim != 128 || b.head_dim != 128) return DA_ERR_UNSUPPORTED;
-    if (a.kv_dtype != DA_F32 && a.kv_dtype != DA_BF16) return DA_ERR_UNSUPPORTED;
+    if (a.kv_dtype < DA_F32 || a.kv_dtype > DA_F16) return DA_ERR_UNSUPPORTED;
     if (a.kv_dtype != b.kv_dtype || a.num_kv_heads != b.num_kv_heads || a.block_tokens != b.block_tokens)
         return DA_ERR_INVALID_ARG;
-    const int64_t esize = a.kv_dtype == DA_BF16 ? 2 : 4;
+    const int64_t esize = a.kv_dtype == DA_F32 ? 4 : 2;
     if (!da::layout_ok(a, esize) || !da::layout_ok(b, esize)) return DA_ERR_INVALID_ARG;
     if (((uintptr_t)k_src | (uintptr_t)v_src | (uintptr_t)k_dst | (uintptr_t)v_dst) & 15) return DA_ERR_INVALID_ARG;
     if (num_blocks == 0) return DA_OK;

@@ -43,14 +43,13 @@ da_status validate_problem(const da_problem &p)
         return DA_ERR_INVALID_ARG;
     if (p.num_q_heads % p.num_kv_heads != 0) return DA_ERR_INVALID_ARG;
     if (!std::isfinite(p.scale)) return DA_ERR_INVALID_ARG;
-    if ((p.kv_dtype != DA_F32 && p.kv_dtype != DA_BF16) || (p.q_dtype != DA_F32 && p.q_dtype != DA_BF16))
-        return DA_ERR_UNSUPPORTED;
+    if (p.kv_dtype < DA_F32 || p.kv_dtype > DA_F16 || p.q_dtype < DA_F32 || p.q_dtype > DA_F16) return DA_ERR_UNSUPPORTED;
     if (p.head_dim != 128) return DA_ERR_UNSUPPORTED;
     if (p.block_tokens % 16 != 0) return DA_ERR_UNSUPPORTED;
     if (p.num_q_heads / p.num_kv_heads > 64) return DA_ERR_UNSUPPORTED;
     if (p.q_len < 0) return DA_ERR_INVALID_ARG;
     if (p.q_len > 128) return DA_ERR_UNSUPPORTED;
-    const int64_t esize = p.kv_dtype == DA_BF16 ? 2 : 4;
+    const int64_t esize = p.kv_dtype == DA_F32 ? 4 : 2;
     if (p.kv_token_stride < p.head_dim || p.kv_head_stride < 0 || p.kv_block_stride < 0) return DA_ERR_INVALID_ARG;
     if ((p.kv_token_stride * esize) % 16 || (p.kv_head_stride * esize) % 16 || (p.kv_block_stride * esize) % 16)
         return DA_ERR_INVALID_ARG;
@@ -75,7 +74,7 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
 
     // kernel family, head tile, workgroup size
     int kernel = tuning.kernel;
-    const bool mfma_ok = p.kv_dtype == DA_BF16 && p.q_dtype == DA_BF16;
+    const bool mfma_ok = p.kv_dtype != DA_F32 && p.q_dtype == p.kv_dtype;  // one 16-bit type throughout
     // bf16 q and K/V go to the matrix-core kernel whatever the group size: even with one live column per tile it
     // streams about 1 % faster than the vector-ALU kernel
     if (kernel == DA_KERNEL_AUTO) kernel = mfma_ok ? DA_KERNEL_MFMA : DA_KERNEL_VALU;

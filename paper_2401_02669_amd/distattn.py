@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdistattn.so")
 
 DA_OK, DA_ERR_INVALID_ARG, DA_ERR_UNSUPPORTED, DA_ERR_WORKSPACE, DA_ERR_HIP, DA_ERR_NO_SPACE = range(6)
-DA_F32, DA_BF16 = 0, 1
+DA_F32, DA_BF16, DA_F16 = 0, 1, 2
 DA_KERNEL_AUTO, DA_KERNEL_VALU, DA_KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = [
@@ -105,7 +105,9 @@ def _dtype_code(t):
         return DA_F32
     if t.dtype == torch.bfloat16:
         return DA_BF16
-    raise TypeError("q / K / V must be float32 or bfloat16, got %s" % t.dtype)
+    if t.dtype == torch.float16:
+        return DA_F16
+    raise TypeError("q / K / V must be float32, bfloat16 or float16, got %s" % t.dtype)
 
 
 def make_problem(q, k_pool, block_table, scale):

@@ -69,7 +69,7 @@ def make(r, device="cpu", poison=True):
     seed = BASE_SEED + r["index"]
     rng = np.random.RandomState(seed)
     B, Hq, Hkv, d, T = r["B"], r["Hq"], r["Hkv"], r["d"], r["T"]
-    tdtype = torch.float32 if r["dtype"] == "f32" else torch.bfloat16
+    tdtype = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[r["dtype"]]
     lens = _lengths(r, rng)
     nb = (lens + T - 1) // T
     used = int(nb.sum())
@@ -126,7 +126,7 @@ def make(r, device="cpu", poison=True):
 
 
 def as_numpy(t):
-    """Host numpy view of a tensor; bf16 becomes uint16 bit patterns (what the oracle reads)."""
+    """Host numpy view of a tensor; bf16 becomes uint16 bit patterns (what the oracle reads), half stays float16."""
     t = t.detach().cpu().contiguous()
     if t.dtype == torch.bfloat16:
         return t.view(torch.int16).numpy().view(np.uint16)

@@ -84,9 +84,11 @@ typedef enum { DA_F32 = 0, DA_BF16 = 1, DA_F16 = 2 /* IEEE binary16 */ } da_dtyp
 
 /* MicroAttention kernel families (da_tuning.kernel). */
 typedef enum {
-    DA_KERNEL_AUTO = 0, /* MFMA when q, K and V share a 16-bit type (bf16 or half), VALU otherwise */
+    DA_KERNEL_AUTO = 0, /* MFMA when q, K and V share a 16-bit type, or share fp32 with a query group > 1;
+                           VALU otherwise */
     DA_KERNEL_VALU = 1, /* fp32 vector ALU dot products, wavefront (DPP) reductions */
-    DA_KERNEL_MFMA = 2  /* bf16 matrix-core products for the (q-head group) x (KV tile) contractions */
+    DA_KERNEL_MFMA = 2  /* matrix-core products for the (q-head group) x (KV tile) contractions; q and the pools
+                           must have the same type */
 } da_kernel;
 
 typedef struct {

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdistattn.so")
-SOURCES = ["distattn_api.hip", "micro_attention_valu.hip", "micro_attention_mfma.hip", "combine.hip", "read_probe.hip", "append.hip", "move.hip", "block_pool.cpp", "schedule.cpp", "placement.cpp"]
+SOURCES = ["distattn_api.hip", "micro_attention_valu.hip", "micro_attention_mfma.hip", "micro_attention_mfma_f32.hip", "combine.hip", "read_probe.hip", "append.hip", "move.hip", "block_pool.cpp", "schedule.cpp", "placement.cpp"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fno-gpu-rdc",
     # packed-fp32 instructions are kept off on the test machines

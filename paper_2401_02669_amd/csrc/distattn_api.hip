@@ -12,6 +12,7 @@
 namespace da {
 hipError_t launch_micro_attention_valu(const MicroParams &p, int grid, hipStream_t stream);
 hipError_t launch_micro_attention_mfma(const MicroParams &p, int grid, hipStream_t stream);
+hipError_t launch_micro_attention_mfma_f32(const MicroParams &p, int grid, hipStream_t stream);
 hipError_t launch_combine(const CombineParams &p, hipStream_t stream);
 }  // namespace da
 
@@ -179,7 +180,8 @@ da_status launch_micro(const da_plan *pl, const da::MicroParams &mp, hipStream_t
     if (pl->sched.kernel == DA_KERNEL_VALU)
         e = da::launch_micro_attention_valu(mp, pl->sched.grid, stream);
     else if (pl->sched.kernel == DA_KERNEL_MFMA)
-        e = da::launch_micro_attention_mfma(mp, pl->sched.grid, stream);
+        e = pl->problem.kv_dtype == DA_F32 ? da::launch_micro_attention_mfma_f32(mp, pl->sched.grid, stream)
+                                           : da::launch_micro_attention_mfma(mp, pl->sched.grid, stream);
     return e == hipSuccess ? DA_OK : DA_ERR_HIP;
 }
 

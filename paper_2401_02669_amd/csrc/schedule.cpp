@@ -74,15 +74,18 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
 
     // kernel family, head tile, workgroup size
     int kernel = tuning.kernel;
-    const bool mfma_ok = p.kv_dtype != DA_F32 && p.q_dtype == p.kv_dtype;  // one 16-bit type throughout
-    // bf16 q and K/V go to the matrix-core kernel whatever the group size: even with one live column per tile it
-    // streams about 1 % faster than the vector-ALU kernel
-    if (kernel == DA_KERNEL_AUTO) kernel = mfma_ok ? DA_KERNEL_MFMA : DA_KERNEL_VALU;
+    const bool mfma_ok = p.q_dtype == p.kv_dtype;  // one type throughout
+    // 16-bit q and K/V go to the matrix-core kernel whatever the group size: even with one live column per tile it
+    // streams about 1 % faster than the vector-ALU kernel.  fp32 goes there when a group shares the K/V read
+    // (the vector ALU cannot keep up with 8 q-heads per kv-head); alone, the vector-ALU kernel is as fast.
+    if (kernel == DA_KERNEL_AUTO)
+        kernel = (mfma_ok && (p.kv_dtype != DA_F32 || G > 1)) ? DA_KERNEL_MFMA : DA_KERNEL_VALU;
     if (kernel == DA_KERNEL_MFMA && !mfma_ok) return DA_ERR_UNSUPPORTED;
     s.kernel = kernel;
     s.waves = 4;
     if (kernel == DA_KERNEL_MFMA) {
-        s.head_tile = G > 32 ? 64 : G > 16 ? 32 : 16;  // one, two or four 16-column matrix-core tiles per K/V read
+        // one, two or four 16-column matrix-core tiles per K/V read (fp32: one)
+        s.head_tile = p.kv_dtype == DA_F32 ? 16 : G > 32 ? 64 : G > 16 ? 32 : 16;
     } else {
         s.head_tile = 1;
         while (s.head_tile < G && s.head_tile < 8) s.head_tile *= 2;

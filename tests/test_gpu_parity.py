@@ -120,6 +120,30 @@ def test_group_sizes(G, kernel):
     assert_parity(out, lse, ref_out, ref_lse, "bf16", "G=%d" % G)
 
 
+@pytest.mark.parametrize("G", [2, 3, 8, 16, 24])
+def test_fp32_groups_on_the_matrix_cores(G):
+    lens = [700, 129, 0, 2048, 1, 31, 33]
+    w = synth.make(custom(lens, Hq=2 * G, Hkv=2, T=64, dtype="f32"), DEV)
+    note("case fp32 group G=%d" % G)
+    prob = da.make_problem(w["q"], w["k_pool"], w["block_table"], w["scale"])
+    assert da.plan_schedule(prob, lens)["kernel"] == da.DA_KERNEL_MFMA
+    ref_out, ref_lse = oracle_attention(w)
+    for bps in (0, 1, 3):
+        out, lse, flags = gpu_attention(w, blocks_per_split=bps)
+        assert flags == 0
+        assert_parity(out, lse, ref_out, ref_lse, "f32", "fp32 G=%d bps=%d" % (G, bps))
+    out, lse, flags = gpu_attention(w, kernel=da.DA_KERNEL_VALU)
+    assert_parity(out, lse, ref_out, ref_lse, "f32", "fp32 G=%d valu" % G)
+
+
+def test_fp32_scaled_gqa_workload_with_outlier_keys():
+    w = synth.make(synth.recipe("c3_70b", len_div=64, dtype="f32"), DEV)
+    ref_out, ref_lse = oracle_attention(w)
+    out, lse, flags = gpu_attention(w)
+    assert flags == 0
+    assert_parity(out, lse, ref_out, ref_lse, "f32", "c3_70b/64 fp32")
+
+
 @pytest.mark.parametrize("T", [16, 48, 112, 1024])
 @pytest.mark.parametrize("G", [1, 4])
 def test_block_sizes_give_the_same_answer(T, G):

@@ -223,6 +223,7 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
             }
 
             u32x4 ph[TILES], pl[TILES];  // P^T operands: 8 tokens of this lane group, column ln; high and low 16-bit parts
+            u32x4 ve[4], vo[4];          // V^T operands of the chunk
             float beta[TILES];           // half only: what the chunk's product is multiplied by when it joins acc
 #pragma unroll
             for (int tl = 0; tl < TILES; ++tl) {
@@ -264,23 +265,23 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
                 for (int t = 0; t < 4; ++t) Weights<F16>::split(s[2 * t], s[2 * t + 1], h[t], l[t]);
                 ph[tl] = u32x4{h[0], h[1], h[2], h[3]};
                 pl[tl] = u32x4{l[0], l[1], l[2], l[3]};
-            }
 
-            // O^T += V^T . P^T, 8 MFMA dimension groups; group n takes dims 8*m + n, m = MFMA row
-            u32x4 ve[4], vo[4];
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const uint32_t d0 = vr[0][w], d1 = vr[1][w], d2 = vr[2][w], d3 = vr[3][w];
-                const uint32_t d4 = vr[4][w], d5 = vr[5][w], d6 = vr[6][w], d7 = vr[7][w];
+                // V^T operands, built once per chunk after the first tile's softmax (V has had that long to arrive):
                 // even dim 2w: low halves; odd dim 2w+1: high halves; (token 2t, token 2t+1) per register
-                ve[w] = u32x4{__builtin_amdgcn_perm(d1, d0, 0x05040100u), __builtin_amdgcn_perm(d3, d2, 0x05040100u),
-                              __builtin_amdgcn_perm(d5, d4, 0x05040100u), __builtin_amdgcn_perm(d7, d6, 0x05040100u)};
-                vo[w] = u32x4{__builtin_amdgcn_perm(d1, d0, 0x07060302u), __builtin_amdgcn_perm(d3, d2, 0x07060302u),
-                              __builtin_amdgcn_perm(d5, d4, 0x07060302u), __builtin_amdgcn_perm(d7, d6, 0x07060302u)};
-            }
-            if constexpr (F16) {
+                if (tl == 0) {
 #pragma unroll
-                for (int tl = 0; tl < TILES; ++tl) {
+                    for (int w = 0; w < 4; ++w) {
+                        const uint32_t d0 = vr[0][w], d1 = vr[1][w], d2 = vr[2][w], d3 = vr[3][w];
+                        const uint32_t d4 = vr[4][w], d5 = vr[5][w], d6 = vr[6][w], d7 = vr[7][w];
+                        ve[w] = u32x4{__builtin_amdgcn_perm(d1, d0, 0x05040100u), __builtin_amdgcn_perm(d3, d2, 0x05040100u),
+                                      __builtin_amdgcn_perm(d5, d4, 0x05040100u), __builtin_amdgcn_perm(d7, d6, 0x05040100u)};
+                        vo[w] = u32x4{__builtin_amdgcn_perm(d1, d0, 0x07060302u), __builtin_amdgcn_perm(d3, d2, 0x07060302u),
+                                      __builtin_amdgcn_perm(d5, d4, 0x07060302u), __builtin_amdgcn_perm(d7, d6, 0x07060302u)};
+                    }
+                }
+                // O^T += V^T . P^T for this tile, 8 MFMA dimension groups (group n takes dims 8*m + n, m = MFMA
+                // row); issued here so that the matrix pipe works on it while the vector ALU does the next tile's softmax
+                if constexpr (F16) {
                     f32x4 part[8];  // the chunk's own V^T . P^T, weights relative to the chunk maximum
 #pragma unroll
                     for (int w = 0; w < 4; ++w) {
@@ -292,12 +293,9 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
                     const float b = beta[tl] * Weights<F16>::kUnscale;
 #pragma unroll
                     for (int n = 0; n < 8; ++n) acc[tl][n] += part[n] * b;
-                }
-            } else {
+                } else {
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
-#pragma unroll
-                    for (int tl = 0; tl < TILES; ++tl) {
+                    for (int w = 0; w < 4; ++w) {
                         acc[tl][2 * w] = mfma16<F16>(ve[w], ph[tl], acc[tl][2 * w]);
                         acc[tl][2 * w] = mfma16<F16>(ve[w], pl[tl], acc[tl][2 * w]);
                         acc[tl][2 * w + 1] = mfma16<F16>(vo[w], ph[tl], acc[tl][2 * w + 1]);

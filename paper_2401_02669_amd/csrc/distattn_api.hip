@@ -164,6 +164,7 @@ void fill_micro(const da_plan *pl, da::MicroParams &mp)
     mp.head_tile = pl->sched.head_tile;
     mp.head_tiles = pl->sched.head_tiles;
     mp.per_split = p.num_kv_heads * pl->sched.head_tiles;
+    mp.wave_items = pl->sched.wave_items;
     mp.q_len = p.q_len > 0 ? p.q_len : 1;
     mp.cols = mp.q_len * mp.G;
     mp.q_dtype = p.q_dtype;

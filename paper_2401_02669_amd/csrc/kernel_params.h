@@ -47,6 +47,7 @@ struct MicroParams {
     int32_t q_dtype;            // da_dtype of q
     int32_t kv_dtype;           // da_dtype of the pools
     int32_t direct_out;
+    int32_t wave_items;         // each wavefront takes whole splits of the run (runs of many short splits)
     int32_t per_split;          // Hkv * head_tiles
     int32_t q_len;              // query tokens per request
     int32_t cols;               // (query token, q-head) columns per kv-head: q_len * G

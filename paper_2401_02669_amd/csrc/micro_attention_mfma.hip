@@ -95,10 +95,14 @@ struct Weights<true> {
     }
 };
 
-template <int TILES, bool F16>
+// WAVE_ITEMS: for runs of many short splits.  Each wavefront then takes whole splits of the run (wavefront w the
+// splits w, w + 4, ...) instead of a quarter of every split's chunks: no merge across wavefronts, no barriers, the
+// result goes from registers to memory.
+template <int TILES, bool F16, bool WAVE_ITEMS>
 __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const MicroParams p)
 {
     constexpr int COLS = kHeadTile * TILES;  // columns per work item
+    constexpr int W = WAVE_ITEMS ? 1 : kWaves;  // wavefronts that share an item's chunks
     // cross-wavefront merge buffers (one barrier after they are written, one after they are read)
     __shared__ float lds_m[kWaves][COLS];
     __shared__ float lds_e[kWaves][COLS];
@@ -169,8 +173,11 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
     int e_begin, e_end;
     run_bounds(p, run, e_begin, e_end);
     int round = 0;
-    ItemInfo it = decode_item<kChunk>(p, e_begin, e_end, kvh, ht);
-    Chunk cur = first_chunk<kChunk>(p, it, wave, lane);
+    const int e_first = WAVE_ITEMS ? e_begin + wave : e_begin;  // this wavefront's first split and its stride
+    constexpr int e_step = WAVE_ITEMS ? kWaves : 1;
+    const int cw = WAVE_ITEMS ? 0 : wave;                       // which of an item's chunk slots are this wavefront's
+    ItemInfo it = decode_item<kChunk>(p, e_first, e_end, kvh, ht);
+    Chunk cur = first_chunk<kChunk>(p, it, cw, lane);
     u32x4 kr[8], vr[8], qreg[TILES][4];
     int visible[TILES], visible_next[TILES];  // causal limits of this lane's columns, for the current / next item
     load_k(fetch_of(cur), kr);
@@ -191,14 +198,14 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
         // the item after this one is looked up early, so that its first K chunk can be requested
         // before this item's result is merged
         ++round;
-        const ItemInfo nit = decode_item<kChunk>(p, e_begin + round, e_end, kvh, ht);
-        const Chunk ncur = first_chunk<kChunk>(p, nit, wave, lane);
+        const ItemInfo nit = decode_item<kChunk>(p, e_first + round * e_step, e_end, kvh, ht);
+        const Chunk ncur = first_chunk<kChunk>(p, nit, cw, lane);
 
         // every step issues 8 V loads and 8 K loads; kr always holds the K rows of `cur`
         const bool idle = !cur.valid;  // this wavefront has no chunk in the item
         while (cur.valid) {
             load_v(fetch_of(cur), vr);
-            const Chunk nxt = next_chunk<kChunk, kWaves>(p, it, cur, lane);
+            const Chunk nxt = next_chunk<kChunk, W>(p, it, cur, lane);
             const Fetch kf_next = fetch_of(nxt.valid ? nxt : ncur);  // nothing left at all: row 0 of the pool
 
             // S[token 16*mb + 4*lg + i][column ln] for mb = 0, 1 and every column tile
@@ -309,61 +316,93 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
         if (idle) load_k(fetch_of(ncur), kr);
         load_q(nit, qreg, visible_next);
 
-        // ---- wavefront result: exp-sum over the lane groups; m is already common -----------------
+        if constexpr (WAVE_ITEMS) {
+            // ---- the wavefront owns the item: normalise or store the partial straight from registers ----
+            const bool direct = p.direct_out && it.ns == 1;
 #pragma unroll
-        for (int tl = 0; tl < TILES; ++tl) {
-            float et = e[tl];
-            et += __shfl_xor(et, 16);
-            et += __shfl_xor(et, 32);
-            const int c = tl * kHeadTile + ln;  // column inside the item
-            if (it.ht * COLS + c < p.cols) {
-                if (lg == 0) {
-                    lds_m[wave][c] = m[tl];
-                    lds_e[wave][c] = et;
-                }
+            for (int tl = 0; tl < TILES; ++tl) {
+                float et = e[tl];
+                et += __shfl_xor(et, 16);
+                et += __shfl_xor(et, 32);
+                const Column col = column_of(p, it.ht * COLS + tl * kHeadTile + ln, it.kvh, it.L);
+                if (!col.live) continue;
+                const float m_nat = m[tl] * kLn2;  // base-2 -> natural-log score units (-inf stays -inf)
+                const float f = direct ? ((et > 0.0f) ? 1.0f / et : 0.0f) : 1.0f;
+                float *row = direct ? p.out + ((int64_t)it.r * p.q_len * p.Hq + col.vh) * kHeadDim
+                                    : p.part_o + (it.row_base + (int64_t)col.vh * it.ns + it.j) * kHeadDim;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    float *dst = &lds_o[wave][c][32 * lg + 8 * i];
-                    *(float4 *)dst = make_float4(acc[tl][0][i], acc[tl][1][i], acc[tl][2][i], acc[tl][3][i]);
-                    *(float4 *)(dst + 4) = make_float4(acc[tl][4][i], acc[tl][5][i], acc[tl][6][i], acc[tl][7][i]);
+                    float *dst = row + 32 * lg + 8 * i;
+                    *(float4 *)dst = make_float4(acc[tl][0][i] * f, acc[tl][1][i] * f, acc[tl][2][i] * f, acc[tl][3][i] * f);
+                    *(float4 *)(dst + 4) = make_float4(acc[tl][4][i] * f, acc[tl][5][i] * f, acc[tl][6][i] * f, acc[tl][7][i] * f);
+                }
+                if (lg == 0) {
+                    if (direct) {
+                        if (p.lse) p.lse[(int64_t)it.r * p.q_len * p.Hq + col.vh] = (et > 0.0f) ? m_nat + __logf(et) : kNegInf;
+                    } else {
+                        const int64_t prow = it.row_base + (int64_t)col.vh * it.ns + it.j;
+                        p.part_m[prow] = m_nat;
+                        p.part_e[prow] = et;
+                    }
                 }
             }
-        }
-        __syncthreads();
+        } else {
+            // ---- wavefront result: exp-sum over the lane groups; m is already common -----------------
+    #pragma unroll
+            for (int tl = 0; tl < TILES; ++tl) {
+                float et = e[tl];
+                et += __shfl_xor(et, 16);
+                et += __shfl_xor(et, 32);
+                const int c = tl * kHeadTile + ln;  // column inside the item
+                if (it.ht * COLS + c < p.cols) {
+                    if (lg == 0) {
+                        lds_m[wave][c] = m[tl];
+                        lds_e[wave][c] = et;
+                    }
+    #pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float *dst = &lds_o[wave][c][32 * lg + 8 * i];
+                        *(float4 *)dst = make_float4(acc[tl][0][i], acc[tl][1][i], acc[tl][2][i], acc[tl][3][i]);
+                        *(float4 *)(dst + 4) = make_float4(acc[tl][4][i], acc[tl][5][i], acc[tl][6][i], acc[tl][7][i]);
+                    }
+                }
+            }
+            __syncthreads();
 
-        // ---- merge the wavefronts and write the item's result -------------------------------------
-        const bool direct = p.direct_out && it.ns == 1;
-        int heads = p.cols - it.ht * COLS;
-        heads = heads > COLS ? COLS : heads;
-        for (int idx = tid; idx < heads * kHeadDim; idx += kWaves * 64) {
-            const int g = idx / kHeadDim, col = idx % kHeadDim;
-            float M = lds_m[0][g];
-#pragma unroll
-            for (int w = 1; w < kWaves; ++w) M = fmaxf(M, lds_m[w][g]);
-            const float mu = (M == kNegInf) ? 0.0f : M;
-            float o = 0.0f, E = 0.0f;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
-                const float wgt = fast_exp2(lds_m[w][g] - mu);
-                o = fmaf(lds_o[w][g][col], wgt, o);
-                E = fmaf(lds_e[w][g], wgt, E);
-            }
-            const int vh = column_of(p, it.ht * COLS + g, it.kvh, it.L).vh;
-            const float m_nat = M * kLn2;  // base-2 -> natural-log score units (-inf stays -inf)
-            if (direct) {
-                const int64_t orow = (int64_t)it.r * p.q_len * p.Hq + vh;
-                p.out[orow * kHeadDim + col] = (E > 0.0f) ? o / E : 0.0f;
-                if (col == 0 && p.lse) p.lse[orow] = (E > 0.0f) ? m_nat + __logf(E) : kNegInf;
-            } else {
-                const int64_t prow = it.row_base + (int64_t)vh * it.ns + it.j;
-                p.part_o[prow * kHeadDim + col] = o;
-                if (col == 0) {
-                    p.part_m[prow] = m_nat;
-                    p.part_e[prow] = E;
+            // ---- merge the wavefronts and write the item's result -------------------------------------
+            const bool direct = p.direct_out && it.ns == 1;
+            int heads = p.cols - it.ht * COLS;
+            heads = heads > COLS ? COLS : heads;
+            for (int idx = tid; idx < heads * kHeadDim; idx += kWaves * 64) {
+                const int g = idx / kHeadDim, col = idx % kHeadDim;
+                float M = lds_m[0][g];
+    #pragma unroll
+                for (int w = 1; w < kWaves; ++w) M = fmaxf(M, lds_m[w][g]);
+                const float mu = (M == kNegInf) ? 0.0f : M;
+                float o = 0.0f, E = 0.0f;
+    #pragma unroll
+                for (int w = 0; w < kWaves; ++w) {
+                    const float wgt = fast_exp2(lds_m[w][g] - mu);
+                    o = fmaf(lds_o[w][g][col], wgt, o);
+                    E = fmaf(lds_e[w][g], wgt, E);
+                }
+                const int vh = column_of(p, it.ht * COLS + g, it.kvh, it.L).vh;
+                const float m_nat = M * kLn2;  // base-2 -> natural-log score units (-inf stays -inf)
+                if (direct) {
+                    const int64_t orow = (int64_t)it.r * p.q_len * p.Hq + vh;
+                    p.out[orow * kHeadDim + col] = (E > 0.0f) ? o / E : 0.0f;
+                    if (col == 0 && p.lse) p.lse[orow] = (E > 0.0f) ? m_nat + __logf(E) : kNegInf;
+                } else {
+                    const int64_t prow = it.row_base + (int64_t)vh * it.ns + it.j;
+                    p.part_o[prow * kHeadDim + col] = o;
+                    if (col == 0) {
+                        p.part_m[prow] = m_nat;
+                        p.part_e[prow] = E;
+                    }
                 }
             }
+            __syncthreads();  // the merge buffers are free again
         }
-        __syncthreads();  // the merge buffers are free again
 #pragma unroll
         for (int tl = 0; tl < TILES; ++tl) visible[tl] = visible_next[tl];
         it = nit;
@@ -374,12 +413,16 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
 template <bool F16>
 hipError_t launch_tiles(const MicroParams &p, int grid, hipStream_t stream)
 {
-    if (p.head_tile == kHeadTile)
-        hipLaunchKernelGGL((micro_attention_mfma_kernel<1, F16>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+    if (p.head_tile == kHeadTile && p.wave_items)
+        hipLaunchKernelGGL((micro_attention_mfma_kernel<1, F16, true>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+    else if (p.wave_items)
+        return hipErrorInvalidValue;
+    else if (p.head_tile == kHeadTile)
+        hipLaunchKernelGGL((micro_attention_mfma_kernel<1, F16, false>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     else if (p.head_tile == 2 * kHeadTile)
-        hipLaunchKernelGGL((micro_attention_mfma_kernel<2, F16>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+        hipLaunchKernelGGL((micro_attention_mfma_kernel<2, F16, false>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     else if (p.head_tile == 4 * kHeadTile)
-        hipLaunchKernelGGL((micro_attention_mfma_kernel<4, F16>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+        hipLaunchKernelGGL((micro_attention_mfma_kernel<4, F16, false>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

@@ -18,6 +18,8 @@ namespace da {
 namespace {
 constexpr int kGroupsPerCu = 1;          // persistent MicroAttention workgroups per compute unit (measured: 2 is 1-2 % slower)
 constexpr int64_t kMinRunTiles = 8;      // shortest run worth a workgroup: two tiles per wavefront
+constexpr int kWaveItemsMinPerRun = 32;  // splits per run from which a wavefront takes whole splits ...
+constexpr int kWaveItemsMaxTiles = 128;  // ... if a split holds no more than this many tiles on average
 constexpr int64_t kSplitCostTiles = 4;   // fixed cost of one split (look-up, merge, partial rows), in tiles
 }
 
@@ -196,6 +198,10 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
     s.ranges = (int32_t)s.range_start.size();
     s.range_start.push_back((int32_t)E);
     s.grid = (int32_t)(s.ranges * P);
+    // Many short splits per run: a wavefront takes whole splits (no merge across wavefronts, no barriers).  Needs
+    // enough splits per run that dealing them to four wavefronts comes out even.
+    s.wave_items = kernel == DA_KERNEL_MFMA && p.kv_dtype != DA_F32 && s.head_tile == 16 &&
+                   E >= (int64_t)kWaveItemsMinPerRun * s.ranges && total_tiles <= (int64_t)kWaveItemsMaxTiles * E;
     return DA_OK;
 }
 

@@ -17,6 +17,7 @@ struct Schedule {
     int32_t head_tile = 1;            // q-heads served by one work item
     int32_t head_tiles = 1;           // work items per (split, kv-head)
     int32_t waves = 4;                // wavefronts per MicroAttention workgroup
+    int32_t wave_items = 0;           // 1: each wavefront takes whole splits of its run (many short splits)
     int32_t ranges = 1;               // consecutive runs of splits; range m is read by workgroups m*P .. m*P+P-1
     int32_t grid = 1;                 // workgroups of the MicroAttention launch = ranges * P, P = Hkv * head_tiles
     int32_t max_nsplits = 1;

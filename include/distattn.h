@@ -164,6 +164,12 @@ da_status da_plan_num_partials(const da_plan *plan, int64_t *num_partials);
 da_status da_plan_split(const da_plan *plan, int32_t r, int32_t j, int64_t *first_token, int64_t *end_token);
 /* nsplits[r]. */
 da_status da_plan_nsplits(const da_plan *plan, int32_t r, int32_t *nsplits);
+/*
+ * What the plan's current schedule launches: the MicroAttention kernel family (da_kernel), the columns served per
+ * work item, and whether each wavefront takes whole splits (1; chosen for runs of many short splits) or the four
+ * wavefronts of a workgroup share every split (0).  Any pointer may be NULL.
+ */
+da_status da_plan_describe(const da_plan *plan, int32_t *kernel, int32_t *head_tile, int32_t *wavefront_splits);
 /* Bytes of device workspace da_attention needs (the three part_* arrays, 256-byte aligned each). */
 da_status da_workspace_bytes(const da_plan *plan, size_t *bytes);
 /*

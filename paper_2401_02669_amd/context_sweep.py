@@ -41,6 +41,11 @@ def main():
         run(B, 64, 8, 32768, 256)
     for L in (4096, 32768, 262144):
         run(1, 32, 32, L, 256)
+    # many short requests (what a lending instance serves): the same 8.6 GB in ever shorter pieces
+    for B, L in ((256, 8192), (1024, 2048), (2048, 1024), (4096, 512)):
+        run(B, 32, 8, L, 256)
+    for B, L in ((256, 4096), (1024, 1024), (2048, 512)):
+        run(B, 32, 32, L, 256)
 
 
 if __name__ == "__main__":

@@ -353,6 +353,15 @@ da_status da_plan_split(const da_plan *pl, int32_t r, int32_t j, int64_t *first_
     return DA_OK;
 }
 
+da_status da_plan_describe(const da_plan *pl, int32_t *kernel, int32_t *head_tile, int32_t *wavefront_splits)
+{
+    if (!pl) return DA_ERR_INVALID_ARG;
+    if (kernel) *kernel = pl->sched.kernel;
+    if (head_tile) *head_tile = pl->sched.head_tile;
+    if (wavefront_splits) *wavefront_splits = pl->sched.wave_items;
+    return DA_OK;
+}
+
 da_status da_workspace_bytes(const da_plan *pl, size_t *bytes)
 {
     if (!pl || !bytes) return DA_ERR_INVALID_ARG;

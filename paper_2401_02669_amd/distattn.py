@@ -18,7 +18,7 @@ DA_KERNEL_AUTO, DA_KERNEL_VALU, DA_KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = [
     "da_status_string", "da_plan_schedule", "da_plan_create", "da_plan_update", "da_plan_destroy",
-    "da_plan_num_partials", "da_plan_split", "da_plan_nsplits", "da_workspace_bytes", "da_plan_error",
+    "da_plan_num_partials", "da_plan_split", "da_plan_nsplits", "da_plan_describe", "da_workspace_bytes", "da_plan_error",
     "da_partial", "da_combine", "da_combine_multi", "da_attention", "da_probe_read", "da_append",
     "da_block_pool_create", "da_block_pool_destroy", "da_block_pool_free_count", "da_block_pool_grow",
     "da_block_pool_release", "da_move_blocks",
@@ -71,6 +71,7 @@ def lib():
         L.da_plan_num_partials.argtypes = [vp, i64p]
         L.da_plan_split.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, i64p, i64p]
         L.da_plan_nsplits.argtypes = [vp, ctypes.c_int32, i32p]
+        L.da_plan_describe.argtypes = [vp, i32p, i32p, i32p]
         L.da_workspace_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
         L.da_plan_error.argtypes = [vp, vp, i32p]
         L.da_partial.argtypes = [vp] * 10
@@ -204,6 +205,12 @@ class Plan:
         n = ctypes.c_size_t()
         _check(lib().da_workspace_bytes(self._h, ctypes.byref(n)), "da_workspace_bytes")
         return n.value
+
+    def describe(self):
+        """dict(kernel, head_tile, wavefront_splits) of the current schedule."""
+        k, t, w = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+        _check(lib().da_plan_describe(self._h, ctypes.byref(k), ctypes.byref(t), ctypes.byref(w)), "da_plan_describe")
+        return dict(kernel=k.value, head_tile=t.value, wavefront_splits=w.value)
 
     def nsplits(self, r):
         n = ctypes.c_int32()

@@ -331,3 +331,34 @@ def test_workspace_and_argument_errors_on_device():
                      part_o=small, part_m=small, part_e=small)
     assert e.value.status == da.DA_ERR_INVALID_ARG
     plan.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,dtype", [(2, 2, "bf16"), (8, 2, "bf16"), (8, 2, "f16"), (32, 2, "bf16")])
+def test_many_short_requests_one_wavefront_per_split(Hq, Hkv, dtype):
+    """Hundreds of short requests per run: each wavefront takes whole splits and writes its result from registers.
+    Few compute units, so that a run holds enough splits for that mode; lengths include empty, one token, block
+    edges, and a few long requests that are cut across runs."""
+    rng = np.random.RandomState(11)
+    lens = [int(x) for x in rng.randint(0, 700, size=700)] + [0, 1, 63, 64, 65, 128, 5000, 9000]
+    w = synth.make(custom(lens, Hq=Hq, Hkv=Hkv, T=64, dtype=dtype), DEV)
+    note("case wavefront splits Hq=%d Hkv=%d %s" % (Hq, Hkv, dtype))
+    ref_out, ref_lse = oracle_attention(w)
+    plan = make_plan(w, num_cus=8)
+    d = plan.describe()
+    assert d["kernel"] == da.DA_KERNEL_MFMA and d["head_tile"] == 16 and d["wavefront_splits"] == (1 if Hq // Hkv <= 16 else 0)
+    out, lse = plan.attention(w["q"], w["k_pool"], w["v_pool"], w["block_table"], w["seq_lens"])
+    po, pm, pe = plan.partial(w["q"], w["k_pool"], w["v_pool"], w["block_table"], w["seq_lens"])
+    out2, lse2 = plan.combine(po, pm, pe)
+    torch.cuda.synchronize()
+    assert plan.error_flags() == 0
+    assert max(plan.nsplits(r) for r in range(len(lens))) > 1 or Hq // Hkv > 16
+    plan.close()
+    assert_parity(out.cpu().numpy(), lse.cpu().numpy(), ref_out, ref_lse, dtype, "wavefront splits, fused")
+    assert_parity(out2.cpu().numpy(), lse2.cpu().numpy(), ref_out, ref_lse, dtype, "wavefront splits, two calls")
+    # the same problem with the workgroup-shared walk (all compute units: too few splits per run for the other mode)
+    plan = make_plan(w)
+    assert plan.describe()["wavefront_splits"] == 0
+    out3, lse3 = plan.attention(w["q"], w["k_pool"], w["v_pool"], w["block_table"], w["seq_lens"])
+    torch.cuda.synchronize()
+    plan.close()
+    assert_parity(out3.cpu().numpy(), lse3.cpu().numpy(), ref_out, ref_lse, dtype, "shared walk")

@@ -92,3 +92,17 @@ def test_multi_query_partials_match_micro_attention(kernel):
     np.testing.assert_allclose(pe[live] * adj, e[live], rtol=2e-4)
     num = np.linalg.norm(po[live] * adj[:, None] - MA[live], axis=1)
     assert np.all(num <= 1e-3 * np.linalg.norm(MA[live], axis=1) + 1e-12)
+
+
+def test_multi_query_with_one_wavefront_per_split():
+    """Many short requests, three query tokens each: the wavefront-per-split walk with causal columns."""
+    rng = np.random.RandomState(5)
+    n = 3
+    lens = [int(x) for x in rng.randint(0, 400, size=500)] + [0, 1, 2, 3, 4, 64, 65, 3000]
+    w = make(lens, n, 8, 2, T=64, seed=3)
+    ref_out, ref_lse = ref_of(w)
+    plan, fused, two_step, _ = run_both(w, num_cus=8)
+    assert plan.describe()["wavefront_splits"] == 1
+    plan.close()
+    for (out, lse), what in ((fused, "fused"), (two_step, "two-step")):
+        assert_parity(out, lse, ref_out, ref_lse, "bf16", "wavefront splits, multi-query, " + what)

@@ -15,6 +15,21 @@ FLAGS = [
 ]
 
 
+C_DRIVER = os.path.join(HERE, "c_abi_driver")
+
+
+def build_c_driver(verbose=False):
+    """The plain-C user of the library (tests/c_abi_driver.c), linked against libdistattn.so and the HIP runtime."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O1", "-Wall", os.path.join(os.path.dirname(HERE), "tests", "c_abi_driver.c"),
+           "-I" + os.path.join(rocm, "include"), "-L" + HERE, "-ldistattn", "-L" + os.path.join(rocm, "lib"), "-lamdhip64",
+           "-lm", "-Wl,-rpath," + HERE, "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", C_DRIVER]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return C_DRIVER
+
+
 def build(verbose=False, extra=()):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + FLAGS + list(extra)
@@ -25,6 +40,7 @@ def build(verbose=False, extra=()):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    build_c_driver(verbose)
     return LIB
 
 

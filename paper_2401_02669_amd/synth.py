@@ -9,7 +9,8 @@ The paper evaluates on conversation and long-document traces (Section 7.1,
 Table 1) that are not available; these generators stand in for them, taking
 only the length ranges from that table (a few tokens up to 2000K).
 
-Layout produced: K and V pools ``[num_phys_blocks][Hkv][T][d]`` (contiguous),
+Layout produced: K and V pools ``[num_phys_blocks][Hkv][T][d]``, by default the two halves of one allocation
+``[num_phys_blocks][2][Hkv][T][d]`` (a block's K and V adjacent; ``kv_layout="separate"`` gives two allocations),
 ``block_table`` int32 ``[B][max_blocks]`` with -1 past a request's last block,
 ``seq_lens`` int32 ``[B]``.  Unused physical blocks and the unused tail of a
 partial last block are filled with NaN ("poison"): they must never influence a
@@ -84,8 +85,13 @@ def make(r, device="cpu", poison=True):
 
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
-    k_pool = torch.empty((num_phys, Hkv, T, d), dtype=tdtype, device=device)
-    v_pool = torch.empty_like(k_pool)
+    if r.get("kv_layout", "adjacent") == "adjacent":
+        # one allocation [P][2][Hkv][T][d]: the K rows and the V rows of a block lie next to each other
+        kv_pool = torch.empty((num_phys, 2, Hkv, T, d), dtype=tdtype, device=device)
+        k_pool, v_pool = kv_pool[:, 0], kv_pool[:, 1]
+    else:
+        k_pool = torch.empty((num_phys, Hkv, T, d), dtype=tdtype, device=device)
+        v_pool = torch.empty_like(k_pool)
     chunk = max(1, (64 << 20) // (Hkv * T * d))  # ~64M elements of fp32 scratch at a time
     for lo in range(0, num_phys, chunk):
         hi = min(num_phys, lo + chunk)

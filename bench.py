@@ -176,7 +176,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w["name"], "q_len": args.q_len, "kv_storage": w["dtype"], "batch": w["B"], "q_heads": w["Hq"], "kv_heads": w["Hkv"], "head_dim": 128,
+        "config": {"workload": w["name"], "q_len": args.q_len, "kv_storage": w["dtype"], "kv_layout": "[block][K|V][kv_head][token][dim], one pool" if w["recipe"].get("kv_layout", "adjacent") == "adjacent" else "two pools [block][kv_head][token][dim]", "batch": w["B"], "q_heads": w["Hq"], "kv_heads": w["Hkv"], "head_dim": 128,
                    "block_tokens": w["T"], "tokens_total": int(w["seq_lens_host"].sum()),
                    "max_len": int(w["seq_lens_host"].max()), "kv_bytes": int(kv_bytes),
                    "work_items": sched["num_items"], "workgroups": sched["workgroups"], "partials": sched["num_partials"],

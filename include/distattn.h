@@ -145,8 +145,20 @@ typedef struct da_plan da_plan; /* opaque: split schedule of one batch + its sma
  * there at the latest).  A plan made for slightly different lengths, as in a
  * decode loop that re-plans every few steps, therefore still gives exact
  * results, only a less even balance; da_plan_split reports the planned cut.
- * A plan serves one launch at a time per stream order; it is not to be used
- * from two host threads at once.
+ *
+ * Threads and lifetime.  da_plan_create and da_plan_update leave everything a
+ * launch needs in place (device tables uploaded, or a small schedule kept for
+ * the kernel arguments), and da_partial, da_combine, da_combine_multi,
+ * da_attention and the da_plan_* queries only read the plan: any number of
+ * host threads may call them on one plan at the same time, on any streams,
+ * as long as their outputs and workspaces are distinct.  da_plan_update,
+ * da_plan_error and da_plan_destroy change the plan and need it to themselves:
+ * no other call on the same plan may run beside them.  A launch enqueued
+ * before da_plan_update keeps the schedule it was given if the update is
+ * enqueued on the same stream (or on one ordered after it).  da_plan_destroy
+ * does not wait for the GPU: every launch that used the plan must have
+ * completed, and no captured graph that holds such a launch may be replayed
+ * afterwards (large schedules are read from device tables the plan owns).
  * Errors: DA_ERR_INVALID_ARG / DA_ERR_UNSUPPORTED from validation (before any
  * HIP call), DA_ERR_HIP if the device tables cannot be made.
  */
@@ -291,17 +303,6 @@ da_status da_block_pool_free_count(const da_block_pool *pool, int32_t *count);
 da_status da_block_pool_grow(da_block_pool *pool, int32_t block_tokens, int32_t max_blocks_per_seq,
                              int32_t *block_table_row_host, int32_t cur_len, int32_t new_len);
 da_status da_block_pool_release(da_block_pool *pool, int32_t block_tokens, int32_t *block_table_row_host, int32_t len);
-
-/*
- * Measurement aid, not part of the attention path: streams `bytes` of device memory once with
- * 16-byte-per-lane loads and discards the data, so that a caller can time the HBM read rate a pure
- * streaming kernel sustains on this GPU (the ceiling the MicroAttention kernels are reported against).
- * `workgroups` workgroups of 512 threads walk `segment_bytes` segments round-robin; `variant` picks
- * the loads in flight per wavefront (0: 4, 1: 8, 2: 16, 3: 8 non-temporal, 4: 16 non-temporal).
- * `sink` is 4 bytes of device memory.
- */
-da_status da_probe_read(const void *src, size_t bytes, size_t segment_bytes, int32_t workgroups, int32_t variant,
-                        void *sink, void *stream);
 
 const char *da_status_string(da_status status);
 

@@ -6,7 +6,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdistattn.so")
-SOURCES = ["distattn_api.hip", "micro_attention_valu.hip", "micro_attention_mfma.hip", "micro_attention_mfma_f32.hip", "combine.hip", "read_probe.hip", "append.hip", "move.hip", "block_pool.cpp", "schedule.cpp", "placement.cpp"]
+PROBE_LIB = os.path.join(HERE, "libdistattn_probe.so")  # measurement probes (include/distattn_probe.h), bench-only
+PROBE_SOURCES = ["read_probe.hip"]
+SOURCES = ["distattn_api.hip", "micro_attention_valu.hip", "micro_attention_mfma.hip", "micro_attention_mfma_f32.hip", "combine.hip", "append.hip", "move.hip", "block_pool.cpp", "schedule.cpp", "placement.cpp"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fno-gpu-rdc",
     # packed-fp32 instructions are kept off on the test machines
@@ -37,6 +39,10 @@ def build(verbose=False, extra=()):
         path = os.path.join(CSRC, s)
         cmd += (["-x", "hip", path] if s.endswith(".cpp") else [path])
     cmd += ["-o", LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    cmd = [hipcc] + FLAGS + list(extra) + [os.path.join(CSRC, x) for x in PROBE_SOURCES] + ["-o", PROBE_LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

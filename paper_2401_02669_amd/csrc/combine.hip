@@ -32,7 +32,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const CombineP
     const int slice = blockIdx.x % SLICES;
     const int r = pair / p.Hq;
     const int h = pair % p.Hq;
-    // per-set split count and first partial row of request r (set 0 may carry them in the kernel arguments)
+    // per-set split count and first partial row of request r (a set may carry them in the kernel arguments)
     int ns_of[kMaxPartialSets];
     int64_t base_of[kMaxPartialSets];
     int total = 0;
@@ -41,12 +41,12 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const CombineP
         ns_of[s] = 0;
         base_of[s] = 0;
         if (s < p.num_sets) {
-            if (s == 0 && p.set[0].nsplits == nullptr) {
+            if (p.set[s].nsplits == nullptr) {
                 // read from the kernel-argument segment itself (CombineParams is the only argument)
                 typedef const char __attribute__((address_space(4))) * kernarg_ptr;
                 const kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
-                ns_of[0] = ((const int32_t __attribute__((address_space(4))) *)(ka + offsetof(CombineParams, inline_nsplits)))[r];
-                base_of[0] = ((const int64_t __attribute__((address_space(4))) *)(ka + offsetof(CombineParams, inline_row_base)))[r];
+                ns_of[s] = ((const int32_t __attribute__((address_space(4))) *)(ka + offsetof(CombineParams, inline_nsplits)))[s * kInlineBatch + r];
+                base_of[s] = ((const int64_t __attribute__((address_space(4))) *)(ka + offsetof(CombineParams, inline_row_base)))[s * kInlineBatch + r];
             } else {
                 ns_of[s] = p.set[s].nsplits[r];
                 base_of[s] = p.set[s].row_base[r];

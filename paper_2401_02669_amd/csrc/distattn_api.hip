@@ -47,8 +47,8 @@ struct da_plan {
     da::Schedule sched;
     std::vector<int32_t> lens;  // host lengths the schedule was made from
     size_t cap_entries = 0, cap_ranges = 0;
-    bool inline_ok = false;            // the schedule is small enough to travel in the kernel arguments
-    mutable bool dev_current = false;  // the device tables hold the current schedule
+    bool inline_ok = false;    // the schedule is small enough to travel in the kernel arguments (then the device
+                               // tables are not kept current; otherwise every create / update uploads them)
     char *dev = nullptr;       // device tables (+ error flag at layout.err)
     char *stage[kRing] = {};   // pinned host staging
     hipEvent_t ev[kRing] = {};
@@ -77,19 +77,25 @@ da_status reserve_tables(da_plan *pl, hipStream_t stream)
 {
     const size_t need_e = pl->sched.entries.size(), need_r = (size_t)pl->sched.ranges;
     if (pl->dev && need_e <= pl->cap_entries && need_r <= pl->cap_ranges) return DA_OK;
-    if (pl->dev && hipStreamSynchronize(stream) != hipSuccess) return DA_ERR_HIP;  // earlier launches still read them
+    int32_t pending_err = 0;  // a flag raised under the old tables survives the move to the new ones
+    if (pl->dev) {
+        if (hipStreamSynchronize(stream) != hipSuccess) return DA_ERR_HIP;  // earlier launches still read them
+        if (hipMemcpy(&pending_err, pl->dev + layout_of(pl).err, sizeof pending_err, hipMemcpyDeviceToHost) != hipSuccess)
+            return DA_ERR_HIP;
+    }
     release_tables(pl);
     pl->cap_entries = need_e * 2 + 1024;
     pl->cap_ranges = std::max<size_t>(need_r * 2, 1024);
     const TableLayout lay = layout_of(pl);
     bool ok = hipMalloc((void **)&pl->dev, lay.total) == hipSuccess;
     for (int i = 0; ok && i < kRing; ++i) ok = hipHostMalloc((void **)&pl->stage[i], lay.total, hipHostMallocDefault) == hipSuccess;
-    ok = ok && hipMemsetAsync(pl->dev + lay.err, 0, 32, stream) == hipSuccess;
+    // blocking copy: the flag word is in place before any launch that follows, on whatever stream
+    const int32_t flag_init[8] = {pending_err, 0, 0, 0, 0, 0, 0, 0};
+    ok = ok && hipMemcpy(pl->dev + lay.err, flag_init, sizeof flag_init, hipMemcpyHostToDevice) == hipSuccess;
     return ok ? DA_OK : DA_ERR_HIP;
 }
 
-// Small schedules travel in the kernel arguments; the device tables are then filled only if something
-// asks for them (da_combine_multi).
+// Small schedules travel in the kernel arguments of every launch that needs them.
 bool fits_inline(const da_plan *pl)
 {
     return pl->sched.entries.size() <= (size_t)da::kInlineEntries && pl->sched.ranges <= da::kInlineRuns &&
@@ -120,24 +126,16 @@ da_status upload(da_plan *pl, hipStream_t stream)
         return DA_ERR_HIP;
     if (hipEventRecord(pl->ev[slot], stream) != hipSuccess) return DA_ERR_HIP;
     pl->ev_pending[slot] = true;
-    pl->dev_current = true;
     return DA_OK;
 }
 
-// After a (re-)plan: upload now, or leave it to the kernel arguments.
+// After a (re-)plan: upload now, or leave it to the kernel arguments.  Everything a launch call needs is in place
+// when this returns, so the launch calls only read the plan.
 da_status publish(da_plan *pl, hipStream_t stream)
 {
     pl->inline_ok = fits_inline(pl);
-    pl->dev_current = false;
     if (pl->inline_ok && pl->dev) return DA_OK;  // (the first call still allocates, for the error flag)
     return upload(pl, stream);
-}
-
-// Device tables on demand, for launches that cannot take them inline.
-da_status need_device_tables(const da_plan *pl, hipStream_t stream)
-{
-    if (pl->dev_current) return DA_OK;
-    return upload(const_cast<da_plan *>(pl), stream);
 }
 
 void fill_micro(const da_plan *pl, da::MicroParams &mp)
@@ -186,23 +184,25 @@ da_status launch_micro(const da_plan *pl, const da::MicroParams &mp, hipStream_t
     return e == hipSuccess ? DA_OK : DA_ERR_HIP;
 }
 
-void fill_set(const da_plan *pl, const float *part_o, const float *part_m, const float *part_e, da::PartialSet &ps)
+// Partial set number `i` of an aggregation launch.  A small plan's two tables travel in the kernel arguments, a
+// large plan's were uploaded when it was made.
+void fill_set(const da_plan *pl, const float *part_o, const float *part_m, const float *part_e, da::CombineParams &cp,
+              int i)
 {
-    const TableLayout lay = layout_of(pl);
+    da::PartialSet &ps = cp.set[i];
     ps.part_o = part_o;
     ps.part_m = part_m;
     ps.part_e = part_e;
-    ps.nsplits = (const int32_t *)(pl->dev + lay.nsplits);
-    ps.row_base = (const int64_t *)(pl->dev + lay.row_base);
-}
-
-// Single-set aggregation of a small plan: its two tables travel in the kernel arguments.
-void fill_set_inline(const da_plan *pl, da::CombineParams &cp)
-{
-    cp.set[0].nsplits = nullptr;
-    cp.set[0].row_base = nullptr;
-    std::memcpy(cp.inline_nsplits, pl->sched.nsplits.data(), sizeof(int32_t) * pl->problem.batch);
-    std::memcpy(cp.inline_row_base, pl->sched.row_base.data(), sizeof(int64_t) * pl->problem.batch);
+    if (pl->inline_ok) {
+        ps.nsplits = nullptr;
+        ps.row_base = nullptr;
+        std::memcpy(cp.inline_nsplits[i], pl->sched.nsplits.data(), sizeof(int32_t) * pl->problem.batch);
+        std::memcpy(cp.inline_row_base[i], pl->sched.row_base.data(), sizeof(int64_t) * pl->problem.batch);
+    } else {
+        const TableLayout lay = layout_of(pl);
+        ps.nsplits = (const int32_t *)(pl->dev + lay.nsplits);
+        ps.row_base = (const int64_t *)(pl->dev + lay.row_base);
+    }
 }
 
 void fill_combine(const da_plan *pl, da::CombineParams &cp)
@@ -210,6 +210,43 @@ void fill_combine(const da_plan *pl, da::CombineParams &cp)
     cp.B = pl->problem.batch;
     cp.Hq = pl->problem.num_q_heads * (pl->problem.q_len > 0 ? pl->problem.q_len : 1);  // virtual heads
     cp.col_slices = ((int64_t)cp.B * cp.Hq < 1024) ? 4 : 1;
+}
+
+// MicroAttention into the three part_* arrays laid out in `ws`, then aggregation, on one stream.
+da_status attention_into(const da_plan *pl, const void *q, const void *k_pool, const void *v_pool,
+                         const int32_t *block_table, const int32_t *seq_lens, float *out, float *lse, char *ws,
+                         hipStream_t stream)
+{
+    const size_t n = (size_t)pl->sched.num_partials;
+    float *part_o = (float *)ws;
+    float *part_m = (float *)(ws + align_up(n * da::kHeadDim * sizeof(float), 256));
+    float *part_e = (float *)((char *)part_m + align_up(n * sizeof(float), 256));
+
+    da::MicroParams mp = {};
+    fill_micro(pl, mp);
+    mp.q = q;
+    mp.k_pool = k_pool;
+    mp.v_pool = v_pool;
+    mp.block_table = block_table;
+    mp.seq_lens = seq_lens;
+    mp.part_o = part_o;
+    mp.part_m = part_m;
+    mp.part_e = part_e;
+    mp.out = out;
+    mp.lse = lse;
+    mp.direct_out = 1;
+    da_status st = launch_micro(pl, mp, stream);
+    if (st != DA_OK) return st;
+    if (pl->sched.max_nsplits <= 1) return DA_OK;  // every request was normalised in the MicroAttention kernel
+
+    da::CombineParams cp = {};
+    fill_combine(pl, cp);
+    fill_set(pl, part_o, part_m, part_e, cp, 0);
+    cp.num_sets = 1;
+    cp.out = out;
+    cp.lse = lse;
+    cp.skip_single = 1;
+    return da::launch_combine(cp, stream) == hipSuccess ? DA_OK : DA_ERR_HIP;
 }
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
@@ -411,8 +448,7 @@ da_status da_combine(const da_plan *pl, const float *part_o, const float *part_m
     if (!aligned16(part_o) || !aligned16(out)) return DA_ERR_INVALID_ARG;
     da::CombineParams cp = {};
     fill_combine(pl, cp);
-    fill_set(pl, part_o, part_m, part_e, cp.set[0]);
-    if (pl->inline_ok) fill_set_inline(pl, cp);
+    fill_set(pl, part_o, part_m, part_e, cp, 0);
     cp.num_sets = 1;
     cp.out = out;
     cp.lse = lse;
@@ -432,8 +468,7 @@ da_status da_combine_multi(const da_partial_set *sets, int32_t num_sets, float *
         // every share describes the same queries: same batch, heads and query tokens
         if (a.batch != b.batch || a.num_q_heads != b.num_q_heads || (a.q_len > 0 ? a.q_len : 1) != (b.q_len > 0 ? b.q_len : 1))
             return DA_ERR_INVALID_ARG;
-        if (need_device_tables(s.plan, (hipStream_t)stream) != DA_OK) return DA_ERR_HIP;
-        fill_set(s.plan, s.part_o, s.part_m, s.part_e, cp.set[i]);
+        fill_set(s.plan, s.part_o, s.part_m, s.part_e, cp, i);
     }
     fill_combine(sets[0].plan, cp);
     cp.num_sets = num_sets;
@@ -452,38 +487,7 @@ da_status da_attention(const da_plan *pl, const void *q, const void *k_pool, con
     size_t need = 0;
     da_workspace_bytes(pl, &need);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return DA_ERR_WORKSPACE;
-    const size_t n = (size_t)pl->sched.num_partials;
-    char *ws = (char *)workspace;
-    float *part_o = (float *)ws;
-    float *part_m = (float *)(ws + align_up(n * da::kHeadDim * sizeof(float), 256));
-    float *part_e = (float *)((char *)part_m + align_up(n * sizeof(float), 256));
-
-    da::MicroParams mp = {};
-    fill_micro(pl, mp);
-    mp.q = q;
-    mp.k_pool = k_pool;
-    mp.v_pool = v_pool;
-    mp.block_table = block_table;
-    mp.seq_lens = seq_lens;
-    mp.part_o = part_o;
-    mp.part_m = part_m;
-    mp.part_e = part_e;
-    mp.out = out;
-    mp.lse = lse;
-    mp.direct_out = 1;
-    da_status st = launch_micro(pl, mp, (hipStream_t)stream);
-    if (st != DA_OK) return st;
-    if (pl->sched.max_nsplits <= 1) return DA_OK;  // every request was normalised in the MicroAttention kernel
-
-    da::CombineParams cp = {};
-    fill_combine(pl, cp);
-    fill_set(pl, part_o, part_m, part_e, cp.set[0]);
-    if (pl->inline_ok) fill_set_inline(pl, cp);
-    cp.num_sets = 1;
-    cp.out = out;
-    cp.lse = lse;
-    cp.skip_single = 1;
-    return da::launch_combine(cp, (hipStream_t)stream) == hipSuccess ? DA_OK : DA_ERR_HIP;
+    return attention_into(pl, q, k_pool, v_pool, block_table, seq_lens, out, lse, (char *)workspace, (hipStream_t)stream);
 }
 
 }  // extern "C"

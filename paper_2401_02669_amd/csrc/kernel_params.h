@@ -64,7 +64,7 @@ struct PartialSet {
     const float *part_o;
     const float *part_m;
     const float *part_e;
-    const int32_t *nsplits;   // [B] of the plan that made them; null (set 0 only): CombineParams::inline_*
+    const int32_t *nsplits;   // [B] of the plan that made them; null: CombineParams::inline_* of this set
     const int64_t *row_base;  // [B]
 };
 
@@ -76,8 +76,8 @@ struct CombineParams {
     int32_t B, Hq;  // Hq counts virtual heads (q_len * num_q_heads)
     int32_t skip_single;  // requests with one split were already normalised by the MicroAttention kernel
     int32_t col_slices;   // workgroups per (request, q-head), each owning 128 / col_slices columns
-    int32_t inline_nsplits[kInlineBatch];
-    int64_t inline_row_base[kInlineBatch];
+    int32_t inline_nsplits[kMaxPartialSets][kInlineBatch];
+    int64_t inline_row_base[kMaxPartialSets][kInlineBatch];
 };
 
 }  // namespace da

@@ -1,9 +1,12 @@
+// Measurement probes, built into a library of their own (libdistattn_probe.so), not into the attention library.
+//
 // Read-ceiling probe: streams a device buffer once with the same 16-byte-per-lane loads the
 // MicroAttention kernels use and only adds the words up.  It measures the HBM read rate this GPU
 // sustains for a pure streaming kernel, the practical ceiling the attention kernels are compared to.
+// Copy probe: a plain copy of a known size, against which hardware traffic counters are scaled.
 #include <hip/hip_runtime.h>
 
-#include "../../include/distattn.h"
+#include "../../include/distattn_probe.h"
 
 namespace {
 
@@ -34,7 +37,21 @@ __global__ __launch_bounds__(512) void read_probe_kernel(const u32x4 *src, size_
     if (acc == 0x9E3779B9u) sink[0] = acc;  // keeps the loads alive; practically never taken
 }
 
+// Plain grid-stride copy, 16 bytes per lane and step: reads n16 * 16 bytes and writes as many, each once.
+__global__ __launch_bounds__(256) void copy_probe_kernel(const u32x4 *src, u32x4 *dst, size_t n16)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 }  // namespace
+
+extern "C" da_status da_probe_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (!src || !dst || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return DA_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(copy_probe_kernel, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const u32x4 *)src, (u32x4 *)dst,
+                       bytes / 16);
+    return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
+}
 
 extern "C" da_status da_probe_read(const void *src, size_t bytes, size_t segment_bytes, int32_t workgroups,
                                    int32_t variant, void *sink, void *stream)

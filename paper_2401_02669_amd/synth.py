@@ -38,6 +38,42 @@ WORKLOADS = {
 }
 
 
+def _uniform(index, B, L, Hq, Hkv, T=256, dtype="bf16"):
+    """B requests of L tokens each, shuffled block table, no spare blocks."""
+    return dict(index=index, B=B, Hq=Hq, Hkv=Hkv, d=128, T=T, dtype=dtype, lens=L, shuffle=True, spare_frac=0.0,
+                outlier_frac=0.0)
+
+
+# Further named, seeded recipes: regimes off the five headline workloads that the measurements cover.
+WORKLOADS.update({
+    # the same 8.6 GB of K/V in ever shorter requests (what an instance that hosts many conversations serves)
+    "short_4096x512": _uniform(10, 4096, 512, 32, 8),
+    "short_2048x1024": _uniform(11, 2048, 1024, 32, 8),
+    "short_1024x2048": _uniform(12, 1024, 2048, 32, 8),
+    "short_256x8192": _uniform(13, 256, 8192, 32, 8),
+    "short_mha_2048x512": _uniform(14, 2048, 512, 32, 32),
+    "short_mha_1024x1024": _uniform(15, 1024, 1024, 32, 32),
+    "short_mha_256x4096": _uniform(16, 256, 4096, 32, 32),
+    # small totals (0.5 GB): two launches and ramp / tail weigh in
+    "small_1x131072": _uniform(20, 1, 131072, 64, 8),
+    "small_4x32768": _uniform(21, 4, 32768, 64, 8),
+    # fp32 caches: MHA goes to the vector-ALU kernel, a query group to the fp32 matrix-core kernel
+    "f32_mha_16x16384": _uniform(30, 16, 16384, 32, 32, dtype="f32"),
+    "f32_gqa_4x131072": _uniform(31, 4, 131072, 64, 8, T=512, dtype="f32"),
+})
+
+# Sweeps: lists of (row name, recipe) that bench.py --workload <sweep> times row by row.
+SWEEPS = {
+    # from one short request to one 2M-token request, and over batch sizes at 32K (GQA 64/8, T = 256)
+    "ctx_sweep": [("%dx%d" % (B, L), _uniform(40 + i, B, L, 64, 8)) for i, (B, L) in enumerate(
+        [(1, 1024), (1, 4096), (1, 16384), (1, 32768), (1, 131072), (4, 32768), (1, 524288), (16, 32768),
+         (1, 2000000), (64, 32768)])],
+    "short_sweep": [(n, WORKLOADS[n]) for n in (
+        "short_256x8192", "short_1024x2048", "short_2048x1024", "short_4096x512", "short_mha_256x4096",
+        "short_mha_1024x1024", "short_mha_2048x512")],
+}
+
+
 def recipe(name, len_div=1, **overrides):
     """Recipe of a named workload; ``len_div`` > 1 gives the scaled-down twin (lengths / len_div)."""
     r = dict(WORKLOADS[name])

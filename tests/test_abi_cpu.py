@@ -26,17 +26,20 @@ def problem(B=2, Hq=8, Hkv=2, d=128, T=256, max_blocks=64, num_phys=256, kv=da.D
 
 
 def test_library_exports_every_declared_symbol():
-    from paper_2401_02669_amd import placement
+    from paper_2401_02669_amd import placement, probe
     declared = set()
     for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
         header = open(os.path.join(ROOT, "include", name)).read()
         header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
         declared |= set(re.findall(r"\b(da_[a-z_]+)\s*\(", header))
-    exports = set(da.EXPORTS) | set(placement.EXPORTS)
+    exports = set(da.EXPORTS) | set(placement.EXPORTS) | set(probe.EXPORTS)
     assert declared == exports, declared ^ exports
     L = da.lib()
-    for name in declared:
+    for name in declared - set(probe.EXPORTS):
         assert hasattr(L, name), name
+    for name in probe.EXPORTS:  # the measurement probes live in a library of their own
+        assert hasattr(probe.lib(), name), name
+        assert not hasattr(L, name), name
     assert da.status_string(da.DA_OK) == "ok"
     assert "unsupported" in da.status_string(da.DA_ERR_UNSUPPORTED)
 
@@ -93,7 +96,7 @@ def _tiles(L, T):
 
 
 @pytest.mark.parametrize("name", list(synth.WORKLOADS))
-def test_schedule_properties_on_the_five_workloads(name):
+def test_schedule_properties_on_the_named_workloads(name):
     r = synth.recipe(name)
     rng = np.random.RandomState(synth.BASE_SEED + r["index"])
     lens = synth._lengths(r, rng)
@@ -110,7 +113,7 @@ def test_schedule_properties_on_the_five_workloads(name):
     assert s["num_items"] == sum(_items_per_request(p, int(n), s["kernel"]) for n in ns)
     per_split = _items_per_request(p, 1, s["kernel"])
     assert s["workgroups"] % per_split == 0 and s["workgroups"] <= 256
-    if name != "c1_tiny":
+    if name != "c1_tiny" and not name.startswith("small_"):
         # every compute unit gets its persistent workgroup ...
         assert s["workgroups"] == 256
         runs = 256 // per_split
@@ -119,9 +122,11 @@ def test_schedule_properties_on_the_five_workloads(name):
         # ... every workgroup reads (nearly) the same number of tokens ...
         assert s["max_workgroup_tokens"] <= 1.02 * float(lens.sum()) / runs + 64
         # ... and partial rows (written once, read once) stay a small fraction of the KV bytes
+        # (requests of a few hundred tokens are the exception: their one output row each is all there is)
         partial_bytes = 2.0 * s["num_partials"] * (128 + 2) * 4
-        kv_bytes = float(lens.sum()) * r["Hkv"] * 2 * 128 * 2
-        assert partial_bytes / kv_bytes < 0.01
+        kv_bytes = float(lens.sum()) * r["Hkv"] * 2 * 128 * (4 if r["dtype"] == "f32" else 2)
+        if name.startswith("c"):
+            assert partial_bytes / kv_bytes < 0.01
 
 
 def test_explicit_blocks_per_split_is_honoured():

@@ -249,6 +249,22 @@ da_status da_attention(const da_plan *plan, const void *q, const void *k_pool, c
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * da_attention for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result as da_attention, minus the
+ * workspace: the partial results go to a fixed array of DA_NOALLOC_SCRATCH_BYTES inside the library's device
+ * image (every GPU the library runs on holds one until the process ends).  The call allocates and frees nothing
+ * and launches the same kernels as da_attention.  A plan whose da_workspace_bytes() exceeds
+ * DA_NOALLOC_SCRATCH_BYTES is rejected with DA_ERR_WORKSPACE before anything is launched.
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents (nothing in it needs clearing:
+ * every row that is read was written by the same call first): calls that overlap on one GPU, on different
+ * streams or from different threads, race; order them on one stream or by events.
+ */
+#define DA_NOALLOC_SCRATCH_BYTES ((size_t)8 << 20)
+da_status da_attention_noalloc(const da_plan *plan, const void *q, const void *k_pool, const void *v_pool,
+                               const int32_t *block_table, const int32_t *seq_lens, float *out, float *lse,
+                               void *stream);
+
+/*
  * KV append, the step before attention in every decode iteration (Section 4:
  * the cache is sliced along the sequence dimension so that newly generated
  * tokens join the sub-block layout as they are produced).  k_new / v_new hold

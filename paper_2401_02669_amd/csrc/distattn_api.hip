@@ -2,7 +2,9 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "../../include/distattn.h"
@@ -16,7 +18,36 @@ hipError_t launch_micro_attention_mfma_f32(const MicroParams &p, int grid, hipSt
 hipError_t launch_combine(const CombineParams &p, hipStream_t stream);
 }  // namespace da
 
+// Partial results of da_attention_noalloc.  Every GPU the library runs on holds its own copy of this array, at its
+// own address, until the process ends; host code reaches it only through the address hipGetSymbolAddress returns
+// for the current device (the array's name is not a device address on the host side).
+constexpr size_t kScratchBytes = DA_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];  // per device: address of `scratch` there (null: not asked yet)
+std::mutex g_scratch_mutex;
+
+// Address of `scratch` on the current device; asked once per device.
+da_status scratch_of_current_device(void **ptr)
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return DA_ERR_HIP;
+    if (device < 0 || device >= kMaxDevices) return DA_ERR_UNSUPPORTED;
+    void *p = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        p = g_scratch_ptr[device].load(std::memory_order_relaxed);
+        if (!p) {
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DA_ERR_HIP;
+            g_scratch_ptr[device].store(p, std::memory_order_release);
+        }
+    }
+    *ptr = p;
+    return DA_OK;
+}
 
 constexpr int kRing = 4;  // pinned staging slots for table uploads
 
@@ -488,6 +519,23 @@ da_status da_attention(const da_plan *pl, const void *q, const void *k_pool, con
     da_workspace_bytes(pl, &need);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return DA_ERR_WORKSPACE;
     return attention_into(pl, q, k_pool, v_pool, block_table, seq_lens, out, lse, (char *)workspace, (hipStream_t)stream);
+}
+
+da_status da_attention_noalloc(const da_plan *pl, const void *q, const void *k_pool, const void *v_pool,
+                               const int32_t *block_table, const int32_t *seq_lens, float *out, float *lse,
+                               void *stream)
+{
+    if (!pl || !q || !k_pool || !v_pool || !block_table || !seq_lens || !out) return DA_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out)) return DA_ERR_INVALID_ARG;
+    size_t need = 0;
+    da_workspace_bytes(pl, &need);
+    if (need > kScratchBytes) return DA_ERR_WORKSPACE;  // more partial rows than the fixed array holds
+    void *ws = nullptr;
+    da_status st = scratch_of_current_device(&ws);
+    if (st != DA_OK) return st;
+    // Nothing in the array has to start at zero: the MicroAttention launch writes every partial row the
+    // aggregation reads (empty splits included) before the aggregation launch, in stream order.
+    return attention_into(pl, q, k_pool, v_pool, block_table, seq_lens, out, lse, (char *)ws, (hipStream_t)stream);
 }
 
 }  // extern "C"

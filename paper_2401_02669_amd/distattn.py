@@ -19,7 +19,7 @@ DA_KERNEL_AUTO, DA_KERNEL_VALU, DA_KERNEL_MFMA = 0, 1, 2
 EXPORTS = [
     "da_status_string", "da_plan_schedule", "da_plan_create", "da_plan_update", "da_plan_destroy",
     "da_plan_num_partials", "da_plan_split", "da_plan_nsplits", "da_plan_describe", "da_workspace_bytes", "da_plan_error",
-    "da_partial", "da_combine", "da_combine_multi", "da_attention", "da_append",
+    "da_partial", "da_combine", "da_combine_multi", "da_attention", "da_attention_noalloc", "da_append",
     "da_block_pool_create", "da_block_pool_destroy", "da_block_pool_free_count", "da_block_pool_grow",
     "da_block_pool_release", "da_move_blocks",
 ]
@@ -77,6 +77,7 @@ def lib():
         L.da_partial.argtypes = [vp] * 10
         L.da_combine.argtypes = [vp] * 7
         L.da_attention.argtypes = [vp] * 9 + [ctypes.c_size_t, vp]
+        L.da_attention_noalloc.argtypes = [vp] * 9
         L.da_combine_multi.argtypes = [vp, ctypes.c_int32, vp, vp, vp]
         L.da_append.argtypes = [ctypes.POINTER(DaProblem)] + [vp] * 8
         L.da_move_blocks.argtypes = [ctypes.POINTER(DaProblem)] * 2 + [vp] * 6 + [ctypes.c_int32, vp, vp]
@@ -263,6 +264,13 @@ class Plan:
         st = lib().da_attention(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table), _ptr(seq_lens),
                                 _ptr(out), _ptr(lse), _ptr(workspace), workspace.numel(), _stream_ptr(stream))
         _check(st, "da_attention")
+        return out, lse
+
+    def attention_noalloc(self, q, k_pool, v_pool, block_table, seq_lens, out, lse=None, stream=None):
+        """da_attention_noalloc: the caller passes inputs and outputs only; partials go to the library's fixed array."""
+        st = lib().da_attention_noalloc(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table), _ptr(seq_lens),
+                                        _ptr(out), _ptr(lse), _stream_ptr(stream))
+        _check(st, "da_attention_noalloc")
         return out, lse
 
 

@@ -59,9 +59,10 @@ def cpu_baseline(w, host, budget_s, threads, q_len):
     lens = w["seq_lens_host"].astype(np.int64)
     esize = 4 if w["dtype"] == "f32" else 2
     kw = {}  # (the oracle takes the number of query tokens from q's shape)
-    # cost of a pair is proportional to its length: probe with the shortest non-empty request
-    order = np.argsort(lens)
-    probe_r = int(next((r for r in order if lens[r] > 0), order[-1]))
+    # cost of a pair is proportional to its length: probe with a request of median length (a very short one
+    # would measure the call, not the tokens)
+    order = [r for r in np.argsort(lens) if lens[r] > 0] or [0]
+    probe_r = int(order[len(order) // 2])
     t0 = time.perf_counter()
     oracle.attention(host["q"], host["k_pool"], host["v_pool"], host["block_table"], host["seq_lens"], w["T"],
                      w["scale"], pairs=np.array([[probe_r, 0]], dtype=np.int32), n_threads=1, **kw)
@@ -90,7 +91,7 @@ def cpu_baseline(w, host, budget_s, threads, q_len):
     sample_bytes = float(tok) * 2 * w["d"] * esize / G
     info = dict(value=sample_bytes / dt / 1e9, unit="GB/s", cores=use, kind="oracle",
                 sample="%d of %d (request, q-head) pairs, %d pair-tokens, %.1f s" % (len(pairs), B * Hq * q_len, tok, dt),
-                tokens_per_s=(sample_bytes / w["kv_bytes"]) * B / dt)
+                seconds=round(dt, 6), tokens_per_s=(sample_bytes / w["kv_bytes"]) * B / dt)
     return info, pairs, ref, ref_lse
 
 
@@ -359,7 +360,7 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="all",
-                    help="all (c2_7b c3_70b c4_2m c5_mixed + c1_tiny), one name of synth.WORKLOADS, ctx_sweep, short_sweep")
+                    help="all (c2_7b c3_70b c4_2m c5_mixed + c1_tiny), names of synth.WORKLOADS (comma-separated), ctx_sweep, short_sweep")
     ap.add_argument("--len-div", type=int, default=1, help="divide every length (debug only; result is not the named workload)")
     ap.add_argument("--blocks-per-split", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 VALU, 2 MFMA")
@@ -411,7 +412,7 @@ def main():
         print(json.dumps(base), flush=True)
         return
 
-    names = LARGE + ["c1_tiny"] if args.workload == "all" else [args.workload]
+    names = LARGE + ["c1_tiny"] if args.workload == "all" else args.workload.split(",")
     per, all_ok = {}, True
     for name in names:
         res, ok = run_workload(synth.recipe(name, len_div=args.len_div), args, dev, threads)
@@ -437,7 +438,7 @@ def main():
     if "c1_tiny" in per:
         c1 = per["c1_tiny"]
         base["c1_tiny_latency"] = {"step_us": round(c1["ms_per_step"] * 1e3, 2), "fused_us": round(c1["fused_da_attention_ms"] * 1e3, 2),
-                                   "oracle_single_thread": c1.get("cpu_baseline", {}).get("sample")}
+                                   "oracle_single_thread_us": round(c1.get("cpu_baseline", {}).get("seconds", 0.0) * 1e6, 1)}
     base["per_workload"] = per
     base["device"] = device
     print(json.dumps(base), flush=True)

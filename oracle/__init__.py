@@ -84,7 +84,14 @@ def _dtype_code(a):
     raise TypeError("oracle takes float32, float16 or uint16 (bf16 bits), got %s" % a.dtype)
 
 
-def _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, strides, keep):
+def _pool_strides(a):
+    """Element strides (block, head, token) of a pool array if the oracle can address it in place, else None."""
+    if a.strides[3] != a.itemsize or any(s <= 0 or s % a.itemsize for s in a.strides[:3]):
+        return None
+    return tuple(s // a.itemsize for s in a.strides[:3])
+
+
+def _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, keep):
     q_len = 1
     if q.ndim == 4:  # multi-query form [B][q_len][Hq][d]
         q_len = q.shape[1]
@@ -96,11 +103,15 @@ def _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, stri
     _, Hkv, T, dd = k_pool.shape
     if dd != d or T != block_tokens:
         raise ValueError("pool shape does not match q / block_tokens")
-    if strides is None:
+    # Pools may be views with any positive (block, head, token) strides and contiguous rows, e.g. the K and V
+    # halves of one [P][2][Hkv][T][d] array or pools with padded rows: they are read in place through their
+    # strides (both pools must then share them); anything else is copied to the packed layout first.
+    strides = _pool_strides(k_pool)
+    if strides is None or _pool_strides(v_pool) != strides:
+        k_pool = np.ascontiguousarray(k_pool)
+        v_pool = np.ascontiguousarray(v_pool)
         strides = (Hkv * T * d, T * d, d)
     q = np.ascontiguousarray(q)
-    k_pool = np.ascontiguousarray(k_pool)
-    v_pool = np.ascontiguousarray(v_pool)
     block_table = np.ascontiguousarray(block_table, dtype=np.int32)
     seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
     if _dtype_code(k_pool) != _dtype_code(v_pool):
@@ -119,13 +130,13 @@ def _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, stri
 
 
 def attention(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale,
-              pairs=None, strides=None, n_threads=1):
+              pairs=None, n_threads=1):
     """Eq. 1.  Returns (out, lse) in fp64: [B][Hq][d], [B][Hq]; or [n][d], [n] for ``pairs`` (n x 2: r, h).
 
     q may also be [B][q_len][Hq][d] (several new tokens per request, causal among them): outputs are then
     [B][q_len][Hq][d], [B][q_len][Hq], and a pair's second entry is the virtual head t * Hq + h."""
     keep = []
-    p = _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, strides, keep)
+    p = _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, keep)
     if pairs is None:
         n = p.B * p.Hq * p.q_len
         pairs_ptr = None
@@ -146,7 +157,7 @@ def attention(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale,
 
 
 def micro_attention(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, bounds,
-                    strides=None, n_threads=1):
+                    n_threads=1):
     """Eq. 2 over caller-chosen partitions.
 
     ``bounds[r]`` is the increasing list of token boundaries of request r
@@ -154,7 +165,7 @@ def micro_attention(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scal
     row(r, h, j) = Hq * sum_{r'<r} nparts[r'] + h * nparts[r] + j.
     """
     keep = []
-    p = _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, strides, keep)
+    p = _problem(q, k_pool, v_pool, block_table, seq_lens, block_tokens, scale, keep)
     nparts = np.array([len(b) - 1 for b in bounds], dtype=np.int32)
     flat = np.ascontiguousarray(np.concatenate([np.asarray(b, dtype=np.int64) for b in bounds]))
     rows = int(nparts.sum()) * p.Hq * p.q_len

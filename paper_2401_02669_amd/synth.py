@@ -101,8 +101,21 @@ def _lengths(r, rng):
     return out
 
 
-def make(r, device="cpu", poison=True):
-    """Build the tensors of recipe ``r`` on ``device``.  Returns a dict of torch tensors + metadata."""
+def pool_bytes(r):
+    """Bytes of K pool + V pool that ``make(r)`` allocates (or takes from ``kv_storage``)."""
+    rng = np.random.RandomState(BASE_SEED + r["index"])
+    nb = (_lengths(r, rng) + r["T"] - 1) // r["T"]
+    used = int(nb.sum())
+    num_phys = max(1, used + int(math.ceil(used * r["spare_frac"])))
+    return num_phys * 2 * r["Hkv"] * r["T"] * r["d"] * (4 if r["dtype"] == "f32" else 2)
+
+
+def make(r, device="cpu", poison=True, kv_storage=None):
+    """Build the tensors of recipe ``r`` on ``device``.  Returns a dict of torch tensors + metadata.
+
+    ``kv_storage``: optional 1-D uint8 tensor on ``device`` of at least ``pool_bytes(r)`` bytes to place the pools
+    in (an engine allocates its KV memory once and keeps it; a caller that builds several workloads in one process
+    can do the same)."""
     seed = BASE_SEED + r["index"]
     rng = np.random.RandomState(seed)
     B, Hq, Hkv, d, T = r["B"], r["Hq"], r["Hkv"], r["d"], r["T"]
@@ -121,13 +134,20 @@ def make(r, device="cpu", poison=True):
 
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
+    def storage(shape, first_byte=0):
+        if kv_storage is None:
+            return torch.empty(shape, dtype=tdtype, device=device)
+        nbytes = int(np.prod(shape)) * tdtype.itemsize
+        assert kv_storage.dtype == torch.uint8 and kv_storage.numel() >= first_byte + nbytes
+        return kv_storage[first_byte: first_byte + nbytes].view(tdtype).view(shape)
+
     if r.get("kv_layout", "adjacent") == "adjacent":
         # one allocation [P][2][Hkv][T][d]: the K rows and the V rows of a block lie next to each other
-        kv_pool = torch.empty((num_phys, 2, Hkv, T, d), dtype=tdtype, device=device)
+        kv_pool = storage((num_phys, 2, Hkv, T, d))
         k_pool, v_pool = kv_pool[:, 0], kv_pool[:, 1]
     else:
-        k_pool = torch.empty((num_phys, Hkv, T, d), dtype=tdtype, device=device)
-        v_pool = torch.empty_like(k_pool)
+        k_pool = storage((num_phys, Hkv, T, d))
+        v_pool = storage((num_phys, Hkv, T, d), first_byte=k_pool.numel() * tdtype.itemsize)
     chunk = max(1, (64 << 20) // (Hkv * T * d))  # ~64M elements of fp32 scratch at a time
     for lo in range(0, num_phys, chunk):
         hi = min(num_phys, lo + chunk)

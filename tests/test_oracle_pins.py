@@ -354,3 +354,38 @@ def test_partition_invariant_uneven_with_outliers():
     out2, lse2 = oracle.aggregate(MA, m, e, nparts, w["Hq"])
     np.testing.assert_allclose(out2, out, rtol=1e-12, atol=1e-14)
     np.testing.assert_allclose(lse2, lse, rtol=1e-13, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- pool views read in place
+@pytest.mark.parametrize("dtype", [np.float32, np.uint16])
+def test_strided_pool_views_equal_the_packed_pools_bitwise(dtype):
+    """The oracle reads pools through their (block, head, token) strides.  The same values laid out (a) packed,
+    (b) as the K and V halves of one [P][2][Hkv][T][d] array, (c) with padded token rows and a padded head stride
+    (NaN in every gap) must give bit-identical results: a wrong stride in any of the three positions lands on a gap
+    or on another token's row."""
+    B, Hq, Hkv, L, d, T = 2, 4, 2, 37, 16, 8
+    q, K, V = rand_case(31, B, Hq, Hkv, L, d, dtype)
+    kp, vp, table, lens = contiguous_problem(q, K, V, T)
+    lens = np.array([L, L - 9], dtype=np.int32)
+    bounds = [[0, 5, 21, L], [0, L - 9]]
+    ref = oracle.attention(q, kp, vp, table, lens, T, 0.3)
+    ref_ma = oracle.micro_attention(q, kp, vp, table, lens, T, 0.3, bounds)
+    P = kp.shape[0]
+    nan = 0x7FC0 if dtype == np.uint16 else np.nan
+
+    both = np.full((P, 2, Hkv, T, d), nan, dtype=kp.dtype)          # (b) K | V adjacent per block
+    both[:, 0], both[:, 1] = kp, vp
+    padded_k = np.full((P, Hkv + 1, T + 3, d + 8), nan, dtype=kp.dtype)  # (c) gaps after rows, tokens and heads
+    padded_v = np.full_like(padded_k, nan)
+    padded_k[:, :Hkv, :T, :d], padded_v[:, :Hkv, :T, :d] = kp, vp
+    for tag, (kv, vv) in (("adjacent", (both[:, 0], both[:, 1])),
+                          ("padded", (padded_k[:, :Hkv, :T, :d], padded_v[:, :Hkv, :T, :d]))):
+        assert not kv.flags["C_CONTIGUOUS"]
+        out, lse = oracle.attention(q, kv, vv, table, lens, T, 0.3)
+        assert np.array_equal(out, ref[0]) and np.array_equal(lse, ref[1]), tag
+        ma = oracle.micro_attention(q, kv, vv, table, lens, T, 0.3, bounds)
+        for a, b in zip(ma, ref_ma):
+            assert np.array_equal(a, b), tag
+    # pools whose strides differ from each other fall back to packed copies, same result
+    out, lse = oracle.attention(q, both[:, 0], vp, table, lens, T, 0.3)
+    assert np.array_equal(out, ref[0]) and np.array_equal(lse, ref[1])

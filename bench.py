@@ -209,7 +209,14 @@ def run_workload(recipe, args, dev, threads, arena=None):
 
     ok = True
     if args.cpu_budget > 0:
-        host = dict(q=synth.as_numpy(w["q"]), k_pool=synth.as_numpy(w["k_pool"]), v_pool=synth.as_numpy(w["v_pool"]),
+        # host copies for the oracle, made without a temporary on the device: the one allocation behind both
+        # pools is copied as it is and the oracle reads its K and V halves in place
+        if w["kv_pool"] is not None:
+            host_kv = synth.as_numpy(w["kv_pool"])
+            host_k, host_v = host_kv[:, 0], host_kv[:, 1]
+        else:
+            host_k, host_v = synth.as_numpy(w["k_pool"]), synth.as_numpy(w["v_pool"])
+        host = dict(q=synth.as_numpy(w["q"]), k_pool=host_k, v_pool=host_v,
                     block_table=w["block_table_host"], seq_lens=w["seq_lens_host"])
         one_thread = name.startswith("c1_tiny")  # latency case: the oracle's single-thread time is the figure asked for
         info, pairs, ref, ref_lse = cpu_baseline(w, host, args.cpu_budget, 1 if one_thread else threads, args.q_len)
@@ -297,10 +304,12 @@ def run_sweep(sweep, args, dev):
     rows = []
     stream = torch.cuda.current_stream()
     sptr = ctypes.c_void_p(stream.cuda_stream)
+    # one allocation for the pools of every row (see main)
+    arena = torch.empty((max(synth.pool_bytes(rec) for _, rec in synth.SWEEPS[sweep]) + 4096,), dtype=torch.uint8, device=dev)
     for row_name, rec in synth.SWEEPS[sweep]:
         r = dict(rec)
         r["name"], r["len_div"] = row_name, 1
-        w = synth.make(r, dev, poison=False)
+        w = synth.make(r, dev, poison=False, kv_storage=arena)
         prob = da.make_problem(w["q"], w["k_pool"], w["block_table"], w["scale"])
         lens_list = w["seq_lens_host"].tolist()
         plan = da.Plan(prob, lens_list, kernel=args.kernel)
@@ -332,7 +341,6 @@ def run_sweep(sweep, args, dev):
         print("# %s" % json.dumps(rows[-1]), file=sys.stderr, flush=True)
         plan.close()
         del w, a, ws, out, lse
-        torch.cuda.empty_cache()
     return rows
 
 
@@ -429,8 +437,8 @@ def main():
         print("# %s: %.4f ms/step, %.1f GB/s, roofline frac %.4f, parity %s" % (
             name, res["ms_per_step"], res["value"], res["roofline"]["frac"],
             res.get("parity_on_sample", {}).get("ok", "not checked")), file=sys.stderr, flush=True)
-        if not os.environ.get("BENCH_KEEP_CACHE"):
-            torch.cuda.empty_cache()
+        # (no torch.cuda.empty_cache() here: returning large blocks to the driver in the middle of a process
+        # left every later launch several percent slower on this GPU; torch re-uses what it holds)
 
     ranked = [n for n in names if n in LARGE] or names
     head = per[min(ranked, key=lambda n: per[n]["value"])]

@@ -146,6 +146,7 @@ def make(r, device="cpu", poison=True, kv_storage=None):
         kv_pool = storage((num_phys, 2, Hkv, T, d))
         k_pool, v_pool = kv_pool[:, 0], kv_pool[:, 1]
     else:
+        kv_pool = None
         k_pool = storage((num_phys, Hkv, T, d))
         v_pool = storage((num_phys, Hkv, T, d), first_byte=k_pool.numel() * tdtype.itemsize)
     chunk = max(1, (64 << 20) // (Hkv * T * d))  # ~64M elements of fp32 scratch at a time
@@ -178,6 +179,7 @@ def make(r, device="cpu", poison=True, kv_storage=None):
 
     return dict(
         name=r["name"], recipe=r, q=q, k_pool=k_pool, v_pool=v_pool,
+        kv_pool=kv_pool,  # the one allocation behind both pools ([P][2][Hkv][T][d]) or None
         block_table=torch.as_tensor(table, device=device),
         seq_lens=torch.as_tensor(lens.astype(np.int32), device=device),
         seq_lens_host=lens.astype(np.int32), block_table_host=table,

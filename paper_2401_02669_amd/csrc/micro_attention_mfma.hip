@@ -42,6 +42,10 @@ constexpr float kLn2 = 0.69314718055994530942f;
 constexpr int kHeadTile = 16;  // columns per MFMA tile (N dimension)
 constexpr int kChunk = 32;     // tokens per wavefront step (MFMA K dimension of the PV product)
 constexpr int kWaves = 4;      // wavefronts per workgroup
+// bf16 weights are taken against a reference maximum that follows the running maximum only when that has grown
+// by more than this (base-2 units): weights stay below 2^16, well inside the range of bf16 and fp32, and the
+// accumulator is rescaled a handful of times per split instead of whenever any column's maximum moves
+constexpr float kLazyRescale = 16.0f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
@@ -166,7 +170,10 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
     const uint32_t k_lane_off = (uint32_t)ln * row_bytes + lg * 16;
     // V: lane reads token (16*(jj/4) + 4*lg + jj%4), bytes [16*ln, +16) of the row
     const uint32_t v_lane_off = (uint32_t)(4 * lg) * row_bytes + ln * 16;
-    const float c2 = p.scale_log2e;
+    // scores come out of the matrix cores unscaled; |scale| * log2(e) is applied inside the exponent's fused
+    // multiply-add and a negative scale by negating the raw scores (never 0, so that a masked -inf stays -inf)
+    const float c2 = fmaxf(fabsf(p.scale_log2e), 1.17549435e-38f);
+    const bool negate = p.scale_log2e < 0.0f;
 
     // Every step issues 8 K loads and 8 V loads whatever the chunk: rows past the valid ones re-read
     // the last valid row (their scores are masked), so the loads need no branches.
@@ -200,7 +207,8 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
         for (int tl = 0; tl < TILES; ++tl) {
             const Column col = column_of(p, it.ht * COLS + tl * kHeadTile + ln, it.kvh, it.L);
             const bool live = it.valid && col.live;
-            visible[tl] = live ? col.visible : 0;
+            // columns past the group carry q = 0 and are never written: they take no part in the masking decision
+            visible[tl] = col.live ? col.visible : (1 << 30);
             const uint16_t *q = (const uint16_t *)p.q + ((int64_t)it.r * p.q_len * p.Hq + col.vh) * kHeadDim;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
@@ -231,11 +239,13 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
 
     while (it.valid) {
         float m[TILES];      // running maximum of column ln's scores, base-2 units (all lane groups agree)
+        float mref[TILES];   // bf16: the maximum the weights and sums are currently taken against (<= m)
         float e[TILES];      // this lane's share of the exp-sum (its 8 tokens per chunk)
         f32x4 acc[TILES][8]; // O^T: acc[tl][n][i] = O[column ln of tile tl][dim 32*lg + 8*i + n]
 #pragma unroll
         for (int tl = 0; tl < TILES; ++tl) {
             m[tl] = kNegInf;
+            mref[tl] = kNegInf;
             e[tl] = 0.0f;
 #pragma unroll
             for (int n = 0; n < 8; ++n) acc[tl][n] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -280,38 +290,75 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
             float beta[TILES];           // half only: what the chunk's product is multiplied by when it joins acc
 #pragma unroll
             for (int tl = 0; tl < TILES; ++tl) {
-                // scores in base-2 units (scale * log2(e) applied); rows past the valid or visible tokens masked out
+                // raw scores of this lane's 8 tokens; rows past the valid or visible tokens masked out.  A chunk
+                // that every column of the tile sees in full (all but the last of a request) skips the masking.
                 float s[8];
                 const int rows_seen = min(cur.lim, visible[tl] - cur.tok0);
+                if (negate) {
+                    s0[tl] = -s0[tl];
+                    s1[tl] = -s1[tl];
+                }
+                if (__builtin_amdgcn_ballot_w64(rows_seen < kChunk) == 0) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    s[i] = (4 * lg + i < rows_seen) ? s0[tl][i] * c2 : kNegInf;
-                    s[4 + i] = (16 + 4 * lg + i < rows_seen) ? s1[tl][i] * c2 : kNegInf;
+                    for (int i = 0; i < 4; ++i) {
+                        s[i] = s0[tl][i];
+                        s[4 + i] = s1[tl][i];
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        s[i] = (4 * lg + i < rows_seen) ? s0[tl][i] : kNegInf;
+                        s[4 + i] = (16 + 4 * lg + i < rows_seen) ? s1[tl][i] : kNegInf;
+                    }
                 }
                 float cm = s[0];
 #pragma unroll
                 for (int i = 1; i < 8; ++i) cm = fmaxf(cm, s[i]);
                 cm = fmaxf(cm, __shfl_xor(cm, 16));
                 cm = fmaxf(cm, __shfl_xor(cm, 32));
+                cm *= c2;  // base-2 units from here on
                 const float mn = fmaxf(m[tl], cm);
-                const float mu = (mn == kNegInf) ? 0.0f : mn;
-                const float alpha = fast_exp2(m[tl] - mu);
-                m[tl] = mn;
-                // bf16 has fp32's exponent range: weights are taken against the running maximum.  Half does not:
-                // weights are taken against the chunk's own maximum, so the largest is 1, and the chunk's product
-                // is rescaled by beta when it joins acc.
-                const float ref = F16 ? ((cm == kNegInf) ? 0.0f : cm) : mu;
                 float sum = 0.0f;
+                if constexpr (F16) {
+                    // Half has a narrow exponent: weights are taken against the chunk's own maximum, so the largest
+                    // is 1, and the chunk's product is rescaled by beta when it joins acc.
+                    const float mu = (mn == kNegInf) ? 0.0f : mn;
+                    const float alpha = fast_exp2(m[tl] - mu);
+                    m[tl] = mn;
+                    const float ref = (cm == kNegInf) ? 0.0f : cm;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    s[i] = fast_exp2(s[i] - ref);
-                    sum += s[i];
-                }
-                beta[tl] = F16 ? fast_exp2(ref - mu) : 1.0f;
-                e[tl] = fmaf(e[tl], alpha, F16 ? sum * beta[tl] : sum);
-                if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+                    for (int i = 0; i < 8; ++i) {
+                        s[i] = fast_exp2(fmaf(s[i], c2, -ref));
+                        sum += s[i];
+                    }
+                    // a chunk with nothing visible for this column joins with weight 0 (not exp2(-mu), which
+                    // overflows for strongly negative maxima and would turn its zero sums into NaN)
+                    beta[tl] = (cm == kNegInf) ? 0.0f : fast_exp2(ref - mu);
+                    e[tl] = fmaf(e[tl], alpha, sum * beta[tl]);
+                    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-                    for (int n = 0; n < 8; ++n) acc[tl][n] *= alpha;
+                        for (int n = 0; n < 8; ++n) acc[tl][n] *= alpha;
+                    }
+                } else {
+                    // bf16 has fp32's exponent range: weights are taken against mref, which is moved up (and acc,
+                    // e rescaled) only when the running maximum has left it behind by more than kLazyRescale
+                    m[tl] = mn;
+                    const bool grow = mn > mref[tl] + kLazyRescale;  // also the first chunk with a visible token
+                    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                        const float alpha = grow ? fast_exp2(mref[tl] - mn) : 1.0f;  // 0 when nothing was seen yet
+                        mref[tl] = grow ? mn : mref[tl];
+                        e[tl] *= alpha;
+#pragma unroll
+                        for (int n = 0; n < 8; ++n) acc[tl][n] *= alpha;
+                    }
+                    const float mu = (mref[tl] == kNegInf) ? 0.0f : mref[tl];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        s[i] = fast_exp2(fmaf(s[i], c2, -mu));
+                        sum += s[i];
+                    }
+                    beta[tl] = 1.0f;
+                    e[tl] += sum;
                 }
                 uint32_t h[4], l[4];
 #pragma unroll
@@ -361,6 +408,18 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
         // the last step above requested the first K chunk of the next item
         if (idle) load_k(fetch_of(ncur), kr);
         load_q(nit, qreg, visible_next);
+        if constexpr (!F16) {
+            // sums and accumulator are relative to mref: bring them to the true maximum m
+#pragma unroll
+            for (int tl = 0; tl < TILES; ++tl) {
+                const float f = (m[tl] == kNegInf) ? 1.0f : fast_exp2(mref[tl] - m[tl]);
+                if (__builtin_amdgcn_ballot_w64(f != 1.0f) != 0) {
+                    e[tl] *= f;
+#pragma unroll
+                    for (int n = 0; n < 8; ++n) acc[tl][n] *= f;
+                }
+            }
+        }
 
         if constexpr (WAVE_ITEMS) {
             // ---- the wavefront owns the item: its rows (normalised, or as a partial) wait in shared memory ----

@@ -238,8 +238,9 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
     load_q(it, qreg, visible);
 
     while (it.valid) {
-        float m[TILES];      // running maximum of column ln's scores, base-2 units (all lane groups agree)
-        float mref[TILES];   // bf16: the maximum the weights and sums are currently taken against (<= m)
+        float m[TILES];      // running maximum of column ln's scores, base-2 units (half: all lane groups agree;
+                             // bf16: this lane's own tokens only, joined across the lane groups at the end)
+        float mref[TILES];   // bf16: the maximum the weights and sums are currently taken against (all lane groups agree)
         float e[TILES];      // this lane's share of the exp-sum (its 8 tokens per chunk)
         f32x4 acc[TILES][8]; // O^T: acc[tl][n][i] = O[column ln of tile tl][dim 32*lg + 8*i + n]
 #pragma unroll
@@ -314,12 +315,12 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
                 float cm = s[0];
 #pragma unroll
                 for (int i = 1; i < 8; ++i) cm = fmaxf(cm, s[i]);
-                cm = fmaxf(cm, __shfl_xor(cm, 16));
-                cm = fmaxf(cm, __shfl_xor(cm, 32));
-                cm *= c2;  // base-2 units from here on
-                const float mn = fmaxf(m[tl], cm);
                 float sum = 0.0f;
                 if constexpr (F16) {
+                    cm = fmaxf(cm, __shfl_xor(cm, 16));
+                    cm = fmaxf(cm, __shfl_xor(cm, 32));
+                    cm *= c2;  // base-2 units from here on
+                    const float mn = fmaxf(m[tl], cm);
                     // Half has a narrow exponent: weights are taken against the chunk's own maximum, so the largest
                     // is 1, and the chunk's product is rescaled by beta when it joins acc.
                     const float mu = (mn == kNegInf) ? 0.0f : mn;
@@ -340,13 +341,20 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
                         for (int n = 0; n < 8; ++n) acc[tl][n] *= alpha;
                     }
                 } else {
-                    // bf16 has fp32's exponent range: weights are taken against mref, which is moved up (and acc,
-                    // e rescaled) only when the running maximum has left it behind by more than kLazyRescale
-                    m[tl] = mn;
-                    const bool grow = mn > mref[tl] + kLazyRescale;  // also the first chunk with a visible token
-                    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                        const float alpha = grow ? fast_exp2(mref[tl] - mn) : 1.0f;  // 0 when nothing was seen yet
-                        mref[tl] = grow ? mn : mref[tl];
+                    // bf16 has fp32's exponent range: weights are taken against mref, the reference maximum that the
+                    // four lanes of a column share; m is the lane's own running maximum (its 8 tokens per chunk).
+                    // No lane's weights may pass 2^kLazyRescale: when a lane's maximum has left mref that far behind
+                    // (also: the first chunk with a visible token), the column maximum is found across the lanes and
+                    // acc, e are rescaled to it.  Otherwise the chunk needs no cross-lane step at all.
+                    cm *= c2;  // base-2 units from here on
+                    m[tl] = fmaxf(m[tl], cm);
+                    if (__builtin_amdgcn_ballot_w64(m[tl] > mref[tl] + kLazyRescale) != 0) {
+                        float mc = m[tl];
+                        mc = fmaxf(mc, __shfl_xor(mc, 16));
+                        mc = fmaxf(mc, __shfl_xor(mc, 32));
+                        const bool grow = mc > mref[tl] + kLazyRescale;
+                        const float alpha = grow ? fast_exp2(mref[tl] - mc) : 1.0f;  // 0 when nothing was seen yet
+                        mref[tl] = grow ? mc : mref[tl];
                         e[tl] *= alpha;
 #pragma unroll
                         for (int n = 0; n < 8; ++n) acc[tl][n] *= alpha;
@@ -409,9 +417,11 @@ __global__ __launch_bounds__(kWaves * 64) void micro_attention_mfma_kernel(const
         if (idle) load_k(fetch_of(ncur), kr);
         load_q(nit, qreg, visible_next);
         if constexpr (!F16) {
-            // sums and accumulator are relative to mref: bring them to the true maximum m
+            // sums and accumulator are relative to mref: bring them to the true maximum m (over the column's four lanes)
 #pragma unroll
             for (int tl = 0; tl < TILES; ++tl) {
+                m[tl] = fmaxf(m[tl], __shfl_xor(m[tl], 16));
+                m[tl] = fmaxf(m[tl], __shfl_xor(m[tl], 32));
                 const float f = (m[tl] == kNegInf) ? 1.0f : fast_exp2(mref[tl] - m[tl]);
                 if (__builtin_amdgcn_ballot_w64(f != 1.0f) != 0) {
                     e[tl] *= f;

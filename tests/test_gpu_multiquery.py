@@ -106,3 +106,48 @@ def test_multi_query_with_one_wavefront_per_split():
     plan.close()
     for (out, lse), what in ((fused, "fused"), (two_step, "two-step")):
         assert_parity(out, lse, ref_out, ref_lse, "bf16", "wavefront splits, multi-query, " + what)
+
+
+@pytest.mark.parametrize("n,Hq,Hkv", [(8, 16, 2), (8, 8, 2), (17, 16, 2), (32, 16, 2), (5, 24, 1), (128, 2, 1)])
+def test_many_columns(n, Hq, Hkv):
+    """32 to 256 (query token, q-head) columns per kv-head: up to four column tiles per work item, the K/V read
+    repeated per 64 columns."""
+    lens = [1500, 0, 1, n - 1, n, n + 1, 64, 65, 4100, 33]
+    w = make(lens, n, Hq, Hkv, T=64, seed=100 + n)
+    print("case many columns n=%d Hq=%d Hkv=%d" % (n, Hq, Hkv), flush=True)
+    ref_out, ref_lse = ref_of(w)
+    for bps, cus in ((0, 0), (0, 16), (5, 0)):
+        plan, fused, two_step, _ = run_both(w, blocks_per_split=bps, num_cus=cus)
+        plan.close()
+        for (out, lse), what in ((fused, "fused"), (two_step, "two-step")):
+            assert_parity(out, lse, ref_out, ref_lse, "bf16", "%s n=%d bps=%d cus=%d" % (what, n, bps, cus))
+            for r in (0, 8):  # worst single query token of the long requests
+                for t in (0, n - 1):
+                    _, rel = errors(out[r, t], ref_out[r, t])
+                    assert rel <= TOL["bf16"]["rel_l2"]
+
+
+def test_partials_of_many_columns_report_the_true_maximum():
+    n, Hq = 12, 8   # 48 columns per kv-head
+    w = make([900, 3, 130, 0, 2500], n, Hq, 2, T=32, seed=77)
+    plan, fused, _, (po, pm, pe) = run_both(w, blocks_per_split=2)
+    ref_out, ref_lse = ref_of(w)
+    assert_parity(fused[0], fused[1], ref_out, ref_lse, "bf16", "48 columns")
+    bounds = []
+    for r in range(w["B"]):
+        b = [0]
+        for j in range(plan.nsplits(r)):
+            lo, hi = plan.split(r, j)
+            b.append(hi)
+        bounds.append(b)
+    plan.close()
+    MA, m, e, nparts = oracle.micro_attention(synth.as_numpy(w["q"]), synth.as_numpy(w["k_pool"]), synth.as_numpy(w["v_pool"]),
+                                              w["block_table_host"], w["seq_lens_host"], w["T"], w["scale"], bounds)
+    po, pm, pe = (x.cpu().numpy().astype(np.float64) for x in (po, pm, pe))
+    live = np.isfinite(m)
+    assert np.array_equal(np.isneginf(pm), ~live) and np.all(pe[~live] == 0) and np.all(po[~live] == 0)
+    # m_j is the true maximum of the split (the kernel's held-back reference maximum must not show)
+    np.testing.assert_allclose(pm[live], m[live], rtol=0, atol=2e-5)
+    np.testing.assert_allclose(pe[live], e[live], rtol=3e-4)
+    num = np.linalg.norm(po[live] - MA[live], axis=1)
+    assert np.all(num <= 1e-3 * np.linalg.norm(MA[live], axis=1) + 1e-12)

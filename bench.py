@@ -36,10 +36,12 @@ PARITY_BAR = {"bf16": (2e-3, 1e-3), "f16": (2e-3, 1e-3), "f32": (1e-5, 1e-5)}  #
 def traffic_from_profile(workload):
     """HBM bytes per MicroAttention launch from the committed rocprofv3 --pmc summary of this workload, if any.
     A stored figure from separate counter runs of the same command, not something this run measures."""
-    rel = os.path.join("profiles", "micro_attention_%s_pmc.txt" % workload)
-    path = os.path.join(ROOT, rel)
-    if not os.path.exists(path):
+    import glob
+    found = sorted(glob.glob(os.path.join(ROOT, "profiles", "micro_attention_*_%s.txt" % workload)))
+    if not found:
         return None, None
+    path = found[0]
+    rel = os.path.relpath(path, ROOT)
     vals = {}
     for line in open(path):
         parts = line.split()

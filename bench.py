@@ -364,6 +364,37 @@ def calibrate_copy(args, dev):
                                          "bytes_written_per_copy": n * 4, "copies": 3}}), flush=True)
 
 
+def probe_writes(args, dev):
+    """What small result writes cost a read stream, by write pattern (da_probe_read_write): 8 GiB read as 256 KiB
+    items (512 tokens of one kv-head, bf16 K + V) by 1024 wavefronts, 2 KiB of result per item (4 q-heads)."""
+    import torch
+    from paper_2401_02669_amd import probe
+
+    total, item, frag, wgs = 8 << 30, 256 << 10, 2048, 256
+    src = torch.full((total // 4,), 0x01020304, dtype=torch.int32, device=dev)
+    dst = torch.zeros((total // item * frag // 4,), dtype=torch.int32, device=dev)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream()
+    rows = []
+    per_wave = total // item // (wgs * 4)
+    for what, burst, stag in (("no writes", 0, 0), ("after every item", 1, 0), ("every 4 items", 4, 0),
+                              ("every 16 items", 16, 0), ("every 16 items, each wavefront at its own phase", 16, 1),
+                              ("once, after the last read", per_wave, 0), ("no writes", 0, 0)):
+        best = None
+        for _ in range(6):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            probe.probe_read_write(src, dst, item, frag, wgs, burst, stag, sink)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        rows.append({"writes": what, "burst_items": burst, "staggered": stag, "ms": round(best, 4),
+                     "read_GBps": round(total / best / 1e6, 1), "pct_of_hbm_peak": round(total / best / 1e6 / 80, 2)})
+    print(json.dumps({"probe_writes": {"read_bytes": total, "item_bytes": item, "result_bytes_per_item": frag,
+                                       "written_bytes": total // item * frag, "rows": rows}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -380,6 +411,7 @@ def main():
     ap.add_argument("--no-probe", action="store_true", help="skip the streaming-read probe")
     ap.add_argument("--no-arena", action="store_true", help="allocate every workload's pools afresh instead of placing them in one up-front allocation")
     ap.add_argument("--calibrate-copy", action="store_true")
+    ap.add_argument("--probe-writes", action="store_true", help="time a read stream with result writes in several patterns and exit")
     ap.add_argument("--calibrate-gib", type=float, default=4.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -406,6 +438,9 @@ def main():
 
     if args.calibrate_copy:
         calibrate_copy(args, dev)
+        return
+    if args.probe_writes:
+        probe_writes(args, dev)
         return
 
     base = {"metric": "kv_read_hbm_GBps", "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -34,6 +34,20 @@ da_status da_probe_read(const void *src, size_t bytes, size_t segment_bytes, int
  */
 da_status da_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/*
+ * Streaming reads with small result writes mixed in, the memory pattern of many short requests (Section 5.3: an
+ * instance that lends memory hosts many conversations): `workgroups` x 4 wavefronts each read items of
+ * `item_bytes` (the K/V of one short request and kv-head) from `src` (`bytes` in all, dealt round-robin) and write
+ * `frag_bytes` of result per item into `dst`, after every `burst` items (0 = never; a value >= the items per
+ * wavefront = once, at the end), all wavefronts at the same items (`staggered` = 0) or each at a phase of its own.
+ * Timed by the caller, it shows what the write pattern costs the read stream.  Sizes are multiples of 16 bytes,
+ * pointers 16-byte aligned DEVICE memory, `dst_bytes` >= bytes / item_bytes * frag_bytes.  Errors as for
+ * da_probe_read.
+ */
+da_status da_probe_read_write(const void *src, size_t bytes, void *dst, size_t dst_bytes, size_t item_bytes,
+                              size_t frag_bytes, int32_t workgroups, int32_t burst, int32_t staggered, void *sink,
+                              void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -43,7 +43,60 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const u32x4 *src, u32x4
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// Streaming reads with small writes mixed in.  Wavefront g of the launch reads items g, g + waves, ... of
+// `item16` 16-byte words each (as a wavefront that owns whole splits reads its requests) and, after every
+// `burst` items (staggered != 0: at a phase of its own instead of together with all other wavefronts), writes
+// burst x frag16 words of "results" to its own region of dst.  burst == 0: no writes at all.
+__global__ __launch_bounds__(256) void read_write_probe_kernel(const u32x4 *src, u32x4 *dst, size_t item16, int items_per_wave,
+                                                               int frag16, int burst, int staggered, uint32_t *sink)
+{
+    const int lane = threadIdx.x & 63;
+    const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int nw = gridDim.x * 4;
+    const int phase = (staggered && burst > 0) ? gw % burst : 0;
+    uint32_t acc = 0;
+    int pending = 0;
+    for (int it = 0; it < items_per_wave; ++it) {
+        const u32x4 *p = src + ((size_t)it * nw + gw) * item16;
+        for (size_t i = lane; i < item16; i += 64 * 16) {
+            u32x4 v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                v[u] = u32x4{0u, 0u, 0u, 0u};
+                if (i + u * 64 < item16) v[u] = __builtin_nontemporal_load(p + i + u * 64);
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+        }
+        ++pending;
+        if (burst > 0 && ((it + 1 + phase) % burst == 0 || it + 1 == items_per_wave)) {
+            const u32x4 val = {acc, acc, acc, acc};
+            u32x4 *d = dst + ((size_t)gw * items_per_wave + (it + 1 - pending)) * frag16;
+            for (int i = lane; i < frag16 * pending; i += 64) d[i] = val;
+            pending = 0;
+        }
+    }
+    if (acc == 0x9E3779B9u) sink[0] = acc;
+}
+
 }  // namespace
+
+extern "C" da_status da_probe_read_write(const void *src, size_t bytes, void *dst, size_t dst_bytes, size_t item_bytes,
+                                         size_t frag_bytes, int32_t workgroups, int32_t burst, int32_t staggered,
+                                         void *sink, void *stream)
+{
+    if (!src || !dst || !sink || workgroups < 1 || burst < 0 || item_bytes < 16 || (item_bytes & 15) || frag_bytes < 16 ||
+        (frag_bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15))
+        return DA_ERR_INVALID_ARG;
+    const size_t waves = (size_t)workgroups * 4;
+    const size_t items_per_wave = bytes / item_bytes / waves;
+    if (items_per_wave < 1 || items_per_wave > (1u << 20)) return DA_ERR_INVALID_ARG;
+    if (dst_bytes < waves * items_per_wave * frag_bytes) return DA_ERR_INVALID_ARG;  // every wavefront's region fits
+    hipLaunchKernelGGL(read_write_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)stream,
+                       (const u32x4 *)src, (u32x4 *)dst, item_bytes / 16, (int)items_per_wave, (int)(frag_bytes / 16), burst,
+                       staggered, (uint32_t *)sink);
+    return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
+}
 
 extern "C" da_status da_probe_copy(const void *src, void *dst, size_t bytes, void *stream)
 {

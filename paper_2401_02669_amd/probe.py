@@ -7,7 +7,7 @@ import torch
 from . import distattn as da
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdistattn_probe.so")
-EXPORTS = ["da_probe_read", "da_probe_copy"]
+EXPORTS = ["da_probe_read", "da_probe_copy", "da_probe_read_write"]
 
 _lib = None
 
@@ -22,6 +22,8 @@ def lib():
         vp = ctypes.c_void_p
         L.da_probe_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, vp, vp]
         L.da_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.da_probe_read_write.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_size_t,
+                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
         for name in EXPORTS:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -48,3 +50,12 @@ def probe_copy(src, dst, stream=None):
     st = lib().da_probe_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), nbytes, _stream_ptr(stream))
     if st != da.DA_OK:
         raise da.DistAttnError(st, "da_probe_copy")
+
+
+def probe_read_write(src, dst, item_bytes, frag_bytes, workgroups, burst, staggered, sink, stream=None):
+    """Enqueue one pass of da_probe_read_write over the whole tensor ``src``."""
+    st = lib().da_probe_read_write(ctypes.c_void_p(src.data_ptr()), src.numel() * src.element_size(),
+                                   ctypes.c_void_p(dst.data_ptr()), dst.numel() * dst.element_size(), item_bytes, frag_bytes,
+                                   workgroups, burst, int(bool(staggered)), ctypes.c_void_p(sink.data_ptr()), _stream_ptr(stream))
+    if st != da.DA_OK:
+        raise da.DistAttnError(st, "da_probe_read_write")

@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdistattn.so")
 PROBE_LIB = os.path.join(HERE, "libdistattn_probe.so")  # measurement probes (include/distattn_probe.h), bench-only
 PROBE_SOURCES = ["read_probe.hip"]
-SOURCES = ["distattn_api.hip", "micro_attention_valu.hip", "micro_attention_mfma.hip", "micro_attention_mfma_f32.hip", "combine.hip", "append.hip", "move.hip", "block_pool.cpp", "schedule.cpp", "placement.cpp"]
+SOURCES = ["distattn_api.hip", "micro_attention_valu.hip", "micro_attention_mfma.hip", "micro_attention_mfma_tiles.hip", "micro_attention_mfma_f32.hip", "combine.hip", "append.hip", "move.hip", "block_pool.cpp", "schedule.cpp", "placement.cpp"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fno-gpu-rdc",
     # packed-fp32 instructions are kept off on the test machines

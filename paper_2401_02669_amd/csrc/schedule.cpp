@@ -86,8 +86,9 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
     s.kernel = kernel;
     s.waves = 4;
     if (kernel == DA_KERNEL_MFMA) {
-        // one, two or four 16-column matrix-core tiles per K/V read (fp32: one)
-        s.head_tile = p.kv_dtype == DA_F32 ? 16 : G > 32 ? 64 : G > 16 ? 32 : 16;
+        // one, two or four 16-column matrix-core tiles per K/V read (fp32: one); bf16: eight, four each for
+        // two pairs of wavefronts that read the same chunks
+        s.head_tile = p.kv_dtype == DA_F32 ? 16 : (G > 64 && p.kv_dtype == DA_BF16) ? 128 : G > 32 ? 64 : G > 16 ? 32 : 16;
     } else {
         s.head_tile = 1;
         while (s.head_tile < G && s.head_tile < 8) s.head_tile *= 2;

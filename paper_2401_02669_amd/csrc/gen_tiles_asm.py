@@ -1,24 +1,35 @@
 """Writes tiles_asm.h: the per-chunk instruction streams of the multi-tile matrix-core MicroAttention kernel.
 
-The kernel (micro_attention_mfma_tiles.hip) serves 32 or 64 columns from one K/V read; at that width a chunk's
-vector-ALU work decides the speed, and the compiler's register allocation (it shuttles the accumulators between the
-two halves of the register file on every chunk) more than doubles it.  The chunk body is therefore written out
-instruction by instruction here, with a fixed register map:
+The kernel (micro_attention_mfma_tiles.hip) serves 32, 64 or 128 columns from one K/V read; at that width a chunk's
+vector-ALU and matrix work, not memory, decide the speed, and what the compiler makes of the same arithmetic written
+in C++ (it shuttles the accumulators between the two halves of the register file on every chunk, and keeps matrix
+and vector work apart) takes twice the cycles.  A chunk is therefore written out instruction by instruction here,
+over a fixed register map:
 
   accumulation registers (only the statements below touch them)
     a[0:127]    O^T accumulators, tile t at a[32t:32t+31], dimension group n at +4n
     a[128:191]  Q^T operands, tile t, k-step s at a[128+16t+4s:+3]
-    a[192:255]  K rows, two buffers of 32: load j of buffer b at a[192+32b+4j:+3]
+    a[192:223]  K rows of the chunk being processed (then requested again for the next), load j at a[192+4j:+3]
+    a[224:239]  exp-sums, tile t at a[224+4t:+3] (a row of ones times P^T: all four registers hold the sum)
+    a[240:243]  bf16 ones
   vector registers above the kernel's own allocation limit of 96
     v[96:127]   scores, tile t at v[96+8t:+7] (tokens 4g+i, then 16+4g+i of lane group g)
-    v[128:191]  V rows as loaded, two buffers of 32: load j of buffer b at v[128+32b+4j:+3]
-    v[192:223]  V^T operands: even dims at v[192+4w:+3], odd dims at v[208+4w:+3]
-    v[224:239]  weights of a tile as bf16 pairs, two buffers of (high 4, low 4)
-    v[240:255]  temporaries
+    v[128:159]  V rows as loaded, load j at v[128+4j:+3]
+    v[160:191]  V^T operands: even dims at v[160+4w:+3], odd dims at v[176+4w:+3]
+    v[192:207]  weights of a tile as bf16 pairs, two buffers of (high 4, low 4)
+    v[208:223]  temporaries
+    v[224:235]  per tile: lane's running maximum m, reference maximum mref, and nmu = -mref (0 while mref = -inf)
+    v[236:245]  the lane's byte offsets of its 8 V loads and 2 groups of K loads inside a full chunk
+    v[246:247]  clamps for a chunk whose last rows are not valid
 
-Chunks alternate between the two K / V buffers along a wavefront's whole chunk stream: the statement for a chunk
-in buffer b finds its rows there (requested two chunks ago), and requests the rows of the chunk after the next
-into the registers it has just used, so that a request has two chunk periods to return in.
+Order of a chunk statement (chunk i; the K rows of i were requested by the statement before, its V^T operands built
+there):
+    request the V rows of chunk i+1
+    K.Q^T: tile 0 first, then the other tiles K register by K register, each register requested again (chunk i+1)
+           after its last product; under these products: maximum, (rarely) rescale and weights of tile 0
+    tile after tile: V^T.P^T of tile t (and the ones row) under the maxima / weights of the tiles after it
+    under the last tile's products: the V^T operands of chunk i+1 from its V rows
+so that matrix and vector instructions alternate nearly everywhere.
 
 Run `python gen_tiles_asm.py` after changing it; the header it writes is committed beside it.
 """
@@ -27,6 +38,7 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 MFMA = "v_mfma_f32_16x16x32_bf16"
+CAP = 96  # the kernel's own code is compiled for v[0:95]
 
 
 def a4(i):
@@ -45,154 +57,119 @@ def QOP(t, s):
     return 128 + 16 * t + 4 * s
 
 
-def KOP(b, j):
-    return 192 + 32 * b + 4 * j
+def KOP(j):
+    return 192 + 4 * j
 
 
-CAP = 96                                # the kernel's own code is compiled for v[0:95]
-S = lambda t, i: 96 + 8 * t + i         # noqa: E731  score i (0..7) of tile t
-VR = lambda b, j, w: 128 + 32 * b + 4 * j + w   # noqa: E731  dword w of V load j of buffer b
-VE = lambda w: 192 + 4 * w              # noqa: E731
-VO = lambda w: 208 + 4 * w              # noqa: E731
-PH = lambda b: 224 + 8 * b              # noqa: E731
-PL = lambda b: 228 + 8 * b              # noqa: E731
-T = lambda i: 240 + i                   # noqa: E731
+def ESUM(t):
+    return 224 + 4 * t
 
 
-def interleave(major, minor, per):
-    """major[0], `per` of minor, major[1], ... ; what is left of either stream follows."""
-    out, k = [], 0
-    for ins in major:
-        out.append(ins)
-        out += minor[k:k + per]
-        k += per
-    out += minor[k:]
-    return out
+ONES = 240
 
 
+def S(t, i):
+    return 96 + 8 * t + i
+
+
+def VR(j, w):
+    return 128 + 4 * j + w
+
+
+def VE(w):
+    return 160 + 4 * w
+
+
+def VO(w):
+    return 176 + 4 * w
+
+
+def PH(b):
+    return 192 + 8 * b
+
+
+def PL(b):
+    return 196 + 8 * b
+
+
+def T(i):
+    return 208 + i
+
+
+def M(t):
+    return 224 + t
+
+
+def MREF(t):
+    return 228 + t
+
+
+def NMU(t):
+    return 232 + t
+
+
+def VOFF(j):
+    return 236 + j
+
+
+def KOFF(g):
+    return 244 + g
+
+
+VCL, KCL = 246, 247
 K_ORDER = (0, 4, 1, 5, 2, 6, 3, 7)  # K loads alternate between the chunk's two 16-row halves
+OLD_K = ["K%d" % j for j in K_ORDER]  # what may be outstanding when a statement starts, oldest first
 
 
-# Byte offsets of a lane's loads inside the chunk being requested, computed in the temporaries during the first
-# phase (which has no other use for them): a row past the chunk's last valid one is replaced by that last row.
-KOFF = (T(12), T(13))   # the lane's K rows ln and 16 + ln
-VCLAMP, KCLAMP = T(14), T(15)
+def v_row(j):
+    return 16 * (j >> 2) + (j & 3)   # lane group g reads tokens 16 * (j / 4) + 4 g + j % 4 with its V load j
 
 
-def offsets_preamble():
-    return ["v_add_u32_e32 v%d, %%[last], %%[ln16]" % VCLAMP,
-            "v_add_u32_e32 v%d, %%[last], %%[lg16]" % KCLAMP,
-            "v_min_u32_e32 v%d, %%[klane], v%d" % (KOFF[0], KCLAMP),
-            "v_mad_u32_u24 v%d, 16, %%[rb], %%[klane]" % KOFF[1],
-            "v_min_u32_e32 v%d, v%d, v%d" % (KOFF[1], KOFF[1], KCLAMP)]
+# ---------------------------------------------------------------------------------------------- pieces
+
+def set_offsets():
+    """The lane's offsets inside a full chunk, from the lane constants."""
+    out = ["v_mad_u32_u24 v%d, %d, %%[rb], %%[vlane]" % (VOFF(j), v_row(j)) for j in range(8)]
+    out += ["v_mov_b32_e32 v%d, %%[klane]" % KOFF(0), "v_mad_u32_u24 v%d, 16, %%[rb], %%[klane]" % KOFF(1)]
+    return out
 
 
-def k_load(b, j):
+def clamp_offsets():
+    """For a chunk whose last valid row comes before row 31: rows past it re-read it."""
+    out = ["v_add_u32_e32 v%d, %%[last], %%[ln16]" % VCL, "v_add_u32_e32 v%d, %%[last], %%[lg16]" % KCL]
+    out += ["v_min_u32_e32 v%d, v%d, v%d" % (VOFF(j), VOFF(j), VCL) for j in range(8)]
+    out += ["v_min_u32_e32 v%d, v%d, v%d" % (KOFF(g), KOFF(g), KCL) for g in range(2)]
+    return out
+
+
+def k_load(j, nt):
     off = (" offset:%d" % (64 * (j % 4))) if j % 4 else ""
-    return ("load", "K%d" % j, "global_load_dwordx4 %s, v%d, %%[kbase]%s nt" % (a4(KOP(b, j)), KOFF[j // 4], off))
+    return ("load", "K%d" % j, "global_load_dwordx4 %s, v%d, %%[kbase]%s%s" % (a4(KOP(j)), KOFF(j // 4), off, nt))
 
 
-def v_offset(j):
-    row = 16 * (j >> 2) + (j & 3)   # lane group g reads tokens 16 * (j / 4) + 4 g + j % 4
-    return ["v_mad_u32_u24 v%d, %d, %%[rb], %%[vlane]" % (T(j % 2), row), "v_min_u32_e32 v%d, v%d, v%d" % (T(j % 2), T(j % 2), VCLAMP)]
+def v_load(j, nt):
+    return ("load", "V%d" % j, "global_load_dwordx4 %s, v%d, %%[vbase]%s" % (v4(VR(j, 0)), VOFF(j), nt))
 
 
-def v_load(b, j):
-    return ("load", "V%d" % j, "global_load_dwordx4 %s, v%d, %%[vbase] nt" % (v4(VR(b, j, 0)), T(j % 2)))
+def qk(t, j):
+    half, s = j // 4, j % 4
+    dst = v4(S(t, 4 * half))
+    return "%s %s, %s, %s, %s" % (MFMA, dst, a4(KOP(j)), a4(QOP(t, s)), "0" if s == 0 else dst)
 
 
-def qk_stream(tiles, b):
-    """K . Q^T for all tiles, K register by K register: each is needed just before its first product and requested
-    again (for the next chunk) right after its last.  An accumulator comes up again 2 * tiles products later."""
-    out = []
-    for j in K_ORDER:
-        half, s = j // 4, j % 4
-        out.append(("need", "K%d" % j))
-        for t in range(tiles):
-            dst = v4(S(t, 4 * half))
-            out.append("%s %s, %s, %s, %s" % (MFMA, dst, a4(KOP(b, j)), a4(QOP(t, s)), "0" if s == 0 else dst))
-        out.append(k_load(b, j))
-    return out
-
-
-def perm_stream(b):
-    """V^T operands from the V rows, load pair by load pair: a pair is requested again as soon as it has been used."""
-    out = []
+def perms_of_group(w):
+    """V^T operands of dimension group w (the four registers of its even and of its odd operand; a register pairs
+    the tokens of two V loads)."""
+    out = [("need", "V%d" % j) for j in range(8)]
     for t in range(4):
-        out += [("need", "V%d" % (2 * t)), ("need", "V%d" % (2 * t + 1))]
-        for w in range(4):
-            out.append("v_perm_b32 v%d, v%d, v%d, %%[sel_lo]" % (VE(w) + t, VR(b, 2 * t + 1, w), VR(b, 2 * t, w)))
-            out.append("v_perm_b32 v%d, v%d, v%d, %%[sel_hi]" % (VO(w) + t, VR(b, 2 * t + 1, w), VR(b, 2 * t, w)))
-        out += v_offset(2 * t) + v_offset(2 * t + 1) + [v_load(b, 2 * t), v_load(b, 2 * t + 1)]
-    return out
-
-
-def merge_streams(major, minor):
-    """One instruction of each in turn (markers travel with the instruction after them); leftovers follow."""
-    def units(stream):
-        out, cur = [], []
-        for x in stream:
-            cur.append(x)
-            if isinstance(x, str):
-                out.append(cur)
-                cur = []
-        if cur:
-            out.append(cur)
-        return out
-    a, b = units(major), units(minor)
-    out = []
-    for k in range(max(len(a), len(b))):
-        if k < len(a):
-            out += a[k]
-        if k < len(b):
-            out += b[k]
-    return out
-
-
-def first_phase(tiles, b):
-    return offsets_preamble() + merge_streams(qk_stream(tiles, b), perm_stream(b))
-
-
-def load_order(tiles):
-    return [x[1] for x in first_phase(tiles, 0) if isinstance(x, tuple) and x[0] == "load"]
-
-
-def resolve_waits(stream, tiles):
-    """Turns need / load markers into s_waitcnt vmcnt(n).  Vector loads return in order; when this stream starts, the
-    16 loads of this chunk (issued two statements ago, in load_order) and after them the 16 of the next chunk (issued
-    by the previous statement) may all be outstanding."""
-    order = load_order(tiles)
-    done = -1      # loads of the previous statement up to this index are known to have returned
-    issued = 0     # loads issued by this statement so far
-    out = []
-    for x in stream:
-        if isinstance(x, str):
-            out.append(x)
-        elif x[0] == "load":
-            out.append(x[2])
-            issued += 1
-        else:
-            pos = order.index(x[1])
-            if pos > done:
-                out.append("s_waitcnt vmcnt(%d)" % (len(order) - 1 - pos + len(order) + issued))
-                done = pos
-    return out
-
-
-def loads(tiles, b):
-    """The 16 loads into buffer b alone (and their offsets), in the order the chunk statements issue them."""
-    out = offsets_preamble()
-    for x in first_phase(tiles, b):
-        if isinstance(x, tuple) and x[0] == "load":
-            if x[1][0] == "V":
-                out += v_offset(int(x[1][1:]))
-            out.append(x[2])
+        out.append("v_perm_b32 v%d, v%d, v%d, %%[sel_lo]" % (VE(w) + t, VR(2 * t + 1, w), VR(2 * t, w)))
+        out.append("v_perm_b32 v%d, v%d, v%d, %%[sel_hi]" % (VO(w) + t, VR(2 * t + 1, w), VR(2 * t, w)))
     return out
 
 
 def mask_tile(t):
     """Scores of rows this lane's column may not see become -inf; rs = rows seen - 4 * lane group."""
-    out = []
+    out = ["v_mov_b32_e32 v%d, 0xff800000" % T(15)]
     for i in range(8):
         row = i if i < 4 else 16 + (i - 4)
         out += ["v_cmp_lt_i32_e32 vcc, %d, %%[rs%d]" % (row, t), "s_nop 1",
@@ -200,69 +177,75 @@ def mask_tile(t):
     return out
 
 
-def max_tile(t):
+def max_tile(t, d):
+    """Lane maximum of the tile's 8 scores into m; d := m - mref (more than 16: the weights would run away).
+    Temporaries 12 and 13."""
     s = [S(t, i) for i in range(8)]
-    return ["v_max3_f32 v%d, v%d, v%d, v%d" % (T(0), s[0], s[1], s[2]),
-            "v_max3_f32 v%d, v%d, v%d, v%d" % (T(1), s[3], s[4], s[5]),
-            "v_max3_f32 v%d, v%d, v%d, v%d" % (T(0), T(0), s[6], s[7]),
-            "v_max_f32_e32 v%d, v%d, v%d" % (T(0), T(0), T(1)),
-            "v_mul_f32_e32 v%d, %%[c2], v%d" % (T(0), T(0)),
-            "v_max_f32_e32 %%[m%d], %%[m%d], v%d" % (t, t, T(0)),
-            "v_sub_f32_e32 v%d, %%[m%d], %%[mref%d]" % (T(4 + t), t, t)]
+    return ["v_max3_f32 v%d, v%d, v%d, v%d" % (T(12), s[0], s[1], s[2]),
+            "v_max3_f32 v%d, v%d, v%d, v%d" % (T(13), s[3], s[4], s[5]),
+            "v_max3_f32 v%d, v%d, v%d, v%d" % (T(12), T(12), s[6], s[7]),
+            "v_max_f32_e32 v%d, v%d, v%d" % (T(12), T(12), T(13)),
+            "v_mul_f32_e32 v%d, %%[c2], v%d" % (T(12), T(12)),
+            "v_max_f32_e32 v%d, v%d, v%d" % (M(t), M(t), T(12)),
+            "v_sub_f32_e32 v%d, v%d, v%d" % (d, M(t), MREF(t))]
 
 
 def weights_tile(t, b):
-    """exp2(score * c2 - reference), split into bf16 high and low parts, for tile t into weight buffer b."""
+    """exp2(score * c2 - reference), split into bf16 high and low parts, for tile t into weight buffer b.
+    Temporaries 0..7 only, so that the maxima (12..15) may run beside it."""
     out = []
     for i in range(8):
-        out.append("v_fma_f32 v%d, v%d, %%[c2], %%[nmu%d]" % (T(i), S(t, i), t))
+        out.append("v_fma_f32 v%d, v%d, %%[c2], v%d" % (T(i), S(t, i), NMU(t)))
     for i in range(8):
         out.append("v_exp_f32_e32 v%d, v%d" % (T(i), T(i)))
     for k in range(4):
         out.append("v_cvt_pk_bf16_f32 v%d, v%d, v%d" % (PH(b) + k, T(2 * k), T(2 * k + 1)))
-    for i in range(8):
-        out.append("v_add_f32_e32 %%[e%d], %%[e%d], v%d" % (t, t, T(i)))
     # what the high parts leave: w - high, one dot product per weight (high pair . (-1, 0) + w, high pair . (0, -1) + w)
     for k in range(4):
-        out.append("v_dot2_f32_bf16 v%d, v%d, %%[neg_lo], v%d" % (T(8 + 2 * k), PH(b) + k, T(2 * k)))
-        out.append("v_dot2_f32_bf16 v%d, v%d, %%[neg_hi], v%d" % (T(9 + 2 * k), PH(b) + k, T(2 * k + 1)))
+        out.append("v_dot2_f32_bf16 v%d, v%d, %%[neg_lo], v%d" % (T(2 * k), PH(b) + k, T(2 * k)))
+        out.append("v_dot2_f32_bf16 v%d, v%d, %%[neg_hi], v%d" % (T(2 * k + 1), PH(b) + k, T(2 * k + 1)))
     for k in range(4):
-        out.append("v_cvt_pk_bf16_f32 v%d, v%d, v%d" % (PL(b) + k, T(8 + 2 * k), T(9 + 2 * k)))
+        out.append("v_cvt_pk_bf16_f32 v%d, v%d, v%d" % (PL(b) + k, T(2 * k), T(2 * k + 1)))
     return out
 
 
 def pv_mfmas(t, b):
-    out = []
-    for p in (PH(b), PL(b)):
-        for w in range(4):
+    """O^T += V^T . P^T of tile t (high and low weights) and the ones row, dimension group by dimension group.
+    Returns the products and, per group w, after how many of them the group's V^T operands may be overwritten."""
+    out = ["%s %s, %s, %s, %s" % (MFMA, a4(ESUM(t)), a4(ONES), v4(PH(b)), a4(ESUM(t)))]
+    free_after = {}
+    for w in range(4):
+        for p in (PH(b), PL(b)):
             out.append("%s %s, %s, %s, %s" % (MFMA, a4(ACC(t, 2 * w)), v4(VE(w)), v4(p), a4(ACC(t, 2 * w))))
             out.append("%s %s, %s, %s, %s" % (MFMA, a4(ACC(t, 2 * w + 1)), v4(VO(w)), v4(p), a4(ACC(t, 2 * w + 1))))
-    return out
+        if w == 0:
+            out.append("%s %s, %s, %s, %s" % (MFMA, a4(ESUM(t)), a4(ONES), v4(PL(b)), a4(ESUM(t))))
+        free_after[w] = len(out)
+    return out, free_after
 
 
 def rescale_tile(t, label):
     """The column maximum over its four lanes; when it has left the reference by more than 16, the reference
-    moves up to it and the sums and accumulators of the tile are rescaled."""
-    out = ["ds_bpermute_b32 v%d, %%[bp16], %%[m%d]" % (T(0), t), "s_waitcnt lgkmcnt(0)",
-           "v_max_f32_e32 v%d, v%d, %%[m%d]" % (T(0), T(0), t),
+    moves up to it and the sums and accumulators of the tile are rescaled.  Temporaries 0..14."""
+    out = ["ds_bpermute_b32 v%d, %%[bp16], v%d" % (T(0), M(t)), "s_waitcnt lgkmcnt(0)",
+           "v_max_f32_e32 v%d, v%d, v%d" % (T(0), T(0), M(t)),
            "ds_bpermute_b32 v%d, %%[bp32], v%d" % (T(1), T(0)), "s_waitcnt lgkmcnt(0)",
            "v_max_f32_e32 v%d, v%d, v%d" % (T(0), T(0), T(1)),
-           "v_sub_f32_e32 v%d, v%d, %%[mref%d]" % (T(1), T(0), t),
-           "v_sub_f32_e32 v%d, %%[mref%d], v%d" % (T(2), t, T(0)),
+           "v_sub_f32_e32 v%d, v%d, v%d" % (T(1), T(0), MREF(t)),
+           "v_sub_f32_e32 v%d, v%d, v%d" % (T(2), MREF(t), T(0)),
            "v_exp_f32_e32 v%d, v%d" % (T(2), T(2)),
            "v_cmp_lt_f32_e32 vcc, 0x41800000, v%d" % T(1),
            "s_nop 1",
            "v_cndmask_b32_e32 v%d, 1.0, v%d, vcc" % (T(2), T(2)),
-           "v_cndmask_b32_e32 %%[mref%d], %%[mref%d], v%d, vcc" % (t, t, T(0)),
+           "v_cndmask_b32_e32 v%d, v%d, v%d, vcc" % (MREF(t), MREF(t), T(0)),
            "s_mov_b64 s[100:101], vcc",
            "s_nop 1",
-           "v_cmp_neq_f32_e32 vcc, 0xff800000, %%[mref%d]" % t,
+           "v_cmp_neq_f32_e32 vcc, 0xff800000, v%d" % MREF(t),
            "s_nop 1",
-           "v_cndmask_b32_e64 %%[nmu%d], 0, -%%[mref%d], vcc" % (t, t),
+           "v_cndmask_b32_e64 v%d, 0, -v%d, vcc" % (NMU(t), MREF(t)),
            "s_mov_b64 vcc, s[100:101]",
            "s_cbranch_vccz %sf" % label]
-    out.append("v_mul_f32_e32 %%[e%d], v%d, %%[e%d]" % (t, T(2), t))
-    regs = [ACC(t, n) + i for n in range(8) for i in range(4)]
+    regs = [ACC(t, n) + i for n in range(8) for i in range(4)] + [ESUM(t) + i for i in range(4)]
     for g in range(0, len(regs), 12):
         grp = regs[g:g + 12]
         out += ["v_accvgpr_read_b32 v%d, a%d" % (T(3 + k), r) for k, r in enumerate(grp)]
@@ -272,29 +255,151 @@ def rescale_tile(t, label):
     return out
 
 
-def body(tiles, masked, buf):
-    ins = resolve_waits(first_phase(tiles, buf), tiles)
-    ins += ["s_nop 7"]  # the last scores settle
+# ---------------------------------------------------------------------------------------------- streams
+
+def interleave(major, minor, per):
+    """major[0], `per` of minor, major[1], ... ; what is left of either stream follows.  Markers (tuples) travel with
+    the instruction after them, a label with the instruction before it (a branch out of the stream comes back to
+    the label right behind it: nothing may come between the two); neither counts."""
+    def units(stream):
+        out, cur = [], []
+        for n, x in enumerate(stream):
+            cur.append(x)
+            is_instr = isinstance(x, str) and not x.endswith(":")
+            label_next = n + 1 < len(stream) and isinstance(stream[n + 1], str) and stream[n + 1].endswith(":")
+            if (is_instr or (isinstance(x, str) and x.endswith(":"))) and not label_next and any(
+                    isinstance(y, str) and not y.endswith(":") for y in cur):
+                out.append(cur)
+                cur = []
+        if cur:
+            out.append(cur)
+        return out
+    a, b = units(major), units(minor)
+    out, k = [], 0
+    for u in a:
+        out += u
+        for v in b[k:k + per]:
+            out += v
+        k += per
+    for v in b[k:]:
+        out += v
+    return out
+
+
+def resolve_waits(stream, old_queue):
+    """Turns need / load markers into s_waitcnt vmcnt(n).  Vector loads return in order; when the stream starts, the
+    loads named in old_queue (oldest first) may all be outstanding.  A need means the newest load of that name."""
+    queue = list(old_queue)
+    done = 0                  # this many from the front are known to have returned
+    out = []
+    for x in stream:
+        if isinstance(x, str):
+            out.append(x)
+        elif x[0] == "load":
+            out.append(x[2])
+            queue.append(x[1])
+        else:
+            pos = len(queue) - 1 - queue[::-1].index(x[1])
+            if pos >= done:
+                out.append("s_waitcnt vmcnt(%d)" % (len(queue) - 1 - pos))
+                done = pos + 1
+    return out, queue[done:]
+
+
+def offsets_prologue():
+    """Offsets for the chunk about to be requested: the full-chunk ones, clamped in place when it is not full."""
+    return ["s_cmp_eq_u32 %[full], 0", "s_cbranch_scc1 20f", "21:"]
+
+
+def offsets_epilogue():
+    return ["s_cmp_eq_u32 %[full], 0", "s_cbranch_scc1 22f", "23:"]
+
+
+def offsets_out_of_line():
+    return ["20:"] + clamp_offsets() + ["s_branch 21b", "22:"] + set_offsets() + ["s_branch 23b"]
+
+
+def request_body(nt):
+    """All 16 loads of a chunk and its V^T operands."""
+    s = [v_load(j, nt) for j in range(8)] + [k_load(j, nt) for j in K_ORDER]
+    for w in range(4):
+        s += perms_of_group(w)
+    ins, left = resolve_waits(s, OLD_K)
+    assert left[-8:] == OLD_K, left
+    return offsets_prologue() + ins + offsets_epilogue() + ["s_branch 29f"] + offsets_out_of_line() + ["29:"]
+
+
+def body(tiles, masked, nt):
+    ins = offsets_prologue()
+    # ---- V rows of the next chunk; K.Q^T of tile 0 ------------------------------------------------------------
+    s = [v_load(j, nt) for j in range(8)]
+    for j in K_ORDER:
+        s += [("need", "K%d" % j), qk(0, j)]
+    # ---- K.Q^T of the other tiles, K register by K register, under tile 0's maximum and weights ---------------
+    rest = []
+    for j in K_ORDER:
+        rest += [qk(t, j) for t in range(1, tiles)] + [k_load(j, nt)]
+    side = ["s_nop 1"] * 2   # tile 0's last scores settle under the first products of the other tiles
     if masked:
-        ins += ["s_nop 3", "v_mov_b32_e32 v%d, 0xff800000" % T(15)]
-        for t in range(tiles):
-            ins += mask_tile(t)
+        side += mask_tile(0)
+    side += max_tile(0, T(14))
+    side += ["v_cmp_lt_f32_e32 vcc, 0x41800000, v%d" % T(14), "s_cbranch_vccnz 30f", "31:"]
+    side += weights_tile(0, 0)
+    head = 2 * tiles   # two K registers' worth of products and loads before the side stream starts
+    s += rest[:head] + interleave(rest[head:], side, 3 if tiles == 4 else 8)
+    first, queue = resolve_waits(s, OLD_K)
+    assert queue[-8:] == OLD_K, queue
+    ins += first + offsets_epilogue()
+    # ---- tile after tile: V^T.P^T under the maxima / weights of the tiles after it ------------------------------
     for t in range(tiles):
-        ins += max_tile(t)
-    d = [T(4 + t) for t in range(tiles)]
-    if tiles == 4:
-        ins += ["v_max3_f32 v%d, v%d, v%d, v%d" % (T(0), d[0], d[1], d[2]), "v_max_f32_e32 v%d, v%d, v%d" % (T(0), T(0), d[3])]
-    else:
-        ins += ["v_max_f32_e32 v%d, v%d, v%d" % (T(0), d[0], d[1])]
-    ins += ["v_cmp_lt_f32_e32 vcc, 0x41800000, v%d" % T(0), "s_cbranch_vccnz 10f", "11:"]
-    ins += weights_tile(0, 0)
-    for t in range(tiles):
-        nxt = weights_tile(t + 1, (t + 1) % 2) if t + 1 < tiles else []
-        ins += interleave(pv_mfmas(t, t % 2), nxt, 3)
-    ins += ["s_branch 19f", "10:"]
-    for t in range(tiles):
-        ins += rescale_tile(t, "1%d" % (2 + t))
-    ins += ["s_branch 11b", "19:"]
+        pv, free_after = pv_mfmas(t, t % 2)
+        if t == 0:
+            side = ["s_nop 7"]   # the last scores of the other tiles settle
+            for u in range(1, tiles):
+                if masked:
+                    side += mask_tile(u)
+                side += max_tile(u, T(14) if u == 1 else T(12))
+                if u > 1:
+                    side += ["v_max_f32_e32 v%d, v%d, v%d" % (T(14), T(14), T(12))]
+            side += ["v_cmp_lt_f32_e32 vcc, 0x41800000, v%d" % T(14), "s_cbranch_vccnz 32f", "33:"]
+            side += weights_tile(1, 1)
+            ins += interleave(pv, side, 3)
+        elif t + 1 < tiles:
+            ins += interleave(pv, weights_tile(t + 1, (t + 1) % 2), 2)
+        else:
+            # the last tile's products free the V^T operands group by group; the next chunk's are built behind them
+            s = pv[:free_after[0]]
+            for w in range(3):
+                s += interleave(pv[free_after[w]:free_after[w + 1]], perms_of_group(w), 2)
+            s += perms_of_group(3)
+            last, queue = resolve_waits(s, queue)
+            assert queue == OLD_K, queue
+            ins += last
+    ins += ["s_branch 39f"]
+    ins += ["30:"] + rescale_tile(0, "34") + ["s_branch 31b"]
+    ins += ["32:"]
+    for u in range(1, tiles):
+        ins += rescale_tile(u, "3%d" % (4 + u))
+    ins += ["s_branch 33b"]
+    ins += offsets_out_of_line()
+    ins += ["39:"]
+    return ins
+
+
+def check(ins):
+    """Every marker resolved, every label defined once, every branch pointing the way it says."""
+    labels = [i[:-1] for i in ins if i.endswith(":")]
+    assert len(labels) == len(set(labels)), labels
+    for n, i in enumerate(ins):
+        assert isinstance(i, str), i
+        if i.startswith("s_cbranch") or i.startswith("s_branch"):
+            tgt = i.split()[-1]
+            assert tgt[:-1] in labels, i
+            pos = ins.index(tgt[:-1] + ":")
+            assert (tgt[-1] == "f") == (pos > n), i
+            # a branch out of the stream comes back to the label right behind it
+            if i.split()[-1] in ("30f", "32f", "20f", "22f"):
+                assert ins[n + 1].endswith(":"), (i, ins[n + 1])
     return ins
 
 
@@ -302,13 +407,9 @@ def c_string(ins):
     return "\n".join('        "%s\\n"' % i for i in ins)
 
 
-def state_ops(tiles):
-    return ', '.join('[m%d] "+v"(m[%d]), [mref%d] "+v"(mref[%d]), [nmu%d] "+v"(nmu[%d]), [e%d] "+v"(e[%d])' % (t, t, t, t, t, t, t, t)
-                     for t in range(tiles))
-
-
-LOAD_OPS = ('[vbase] "s"(nl.vb), [kbase] "s"(nl.kb), [last] "s"(nl.last), [rb] "s"(lc.rb), [vlane] "v"(lc.vlane), [klane] "v"(lc.klane), '
-            '[ln16] "v"(lc.ln16), [lg16] "v"(lc.lg16)')
+LOAD_OPS = ('[vbase] "s"(nl.vb), [kbase] "s"(nl.kb), [last] "s"(nl.last), [full] "s"(nl.full), [rb] "s"(lc.rb), '
+            '[vlane] "v"(lc.vlane), [klane] "v"(lc.klane), [ln16] "v"(lc.ln16), [lg16] "v"(lc.lg16), '
+            '[sel_lo] "s"(sel_lo), [sel_hi] "s"(sel_hi)')
 
 
 def emit():
@@ -325,10 +426,11 @@ def emit():
     h.append("// vector registers from this one up, and the whole accumulation file, belong to the statements below")
     h.append("constexpr int kFirstOwnVgpr = %d;" % CAP)
     h.append("")
-    h.append("// what a statement needs to request a chunk's V and K rows: wavefront-uniform ...")
+    h.append("// what a statement needs to request a chunk's V and K rows (all wavefront-uniform) ...")
     h.append("struct NextLoads {")
     h.append("    const char *vb, *kb;   // first row of the chunk in the V / K pool")
     h.append("    uint32_t last;         // byte offset of the chunk's last valid row (rows past it re-read it)")
+    h.append("    uint32_t full;         // 1: all 32 rows are valid")
     h.append("};")
     h.append("// ... and what never changes: K: the lane reads rows ln and 16 + ln, bytes [64 s + 16 g, +16) of k-step s;")
     h.append("// V: rows 16 * (j / 4) + 4 g + j % 4 for its load j, bytes [16 ln, +16)  (g = lane / 16, ln = lane % 16)")
@@ -338,19 +440,25 @@ def emit():
     h.append("    uint32_t ln16, lg16;   // 16 ln; 16 g")
     h.append("};")
     h.append("")
-    h.append("// names the highest registers of both files so that the kernel is given them")
-    h.append("__device__ __forceinline__ void init()")
+    h.append("// once per wavefront: bf16 ones, the lane's load offsets; names the highest registers of both files so that the")
+    h.append("// kernel is given them")
+    h.append("__device__ __forceinline__ void init(const LaneConstants &lc)")
     h.append("{")
-    h.append('    asm volatile("v_mov_b32 v255, 0\\n v_accvgpr_write_b32 a255, v255\\n" ::: "v255", "a255");')
+    h.append("    asm volatile(")
+    h.append(c_string(["v_mov_b32_e32 v255, 0x3f803f80"] + ["v_accvgpr_write_b32 a%d, v255" % (ONES + i) for i in range(4)]
+                      + ["v_accvgpr_write_b32 a255, v255"] + set_offsets()))
+    h.append('        :: [rb] "s"(lc.rb), [vlane] "v"(lc.vlane), [klane] "v"(lc.klane) : "v255", "a255");')
     h.append("}")
     h.append("")
     for tiles in (2, 4):
-        regs = list(range(0, 32 * tiles))
-        h.append("// accumulators of %d tiles := 0" % tiles)
-        h.append("__device__ __forceinline__ void zero_%d()" % tiles)
+        ins = ["v_accvgpr_write_b32 a%d, 0" % r for r in list(range(0, 32 * tiles)) + [ESUM(t) + i for t in range(tiles) for i in range(4)]]
+        for t in range(tiles):
+            ins += ["v_mov_b32_e32 v%d, 0xff800000" % M(t), "v_mov_b32_e32 v%d, 0xff800000" % MREF(t), "v_mov_b32_e32 v%d, 0" % NMU(t)]
+        h.append("// start of an item for %d tiles: accumulators and exp-sums := 0, maxima := -inf" % tiles)
+        h.append("__device__ __forceinline__ void begin_item_%d()" % tiles)
         h.append("{")
         h.append("    asm volatile(")
-        h.append(c_string(["v_accvgpr_write_b32 a%d, 0" % r for r in regs]))
+        h.append(c_string(ins))
         h.append("        ::: );")
         h.append("}")
         h.append("")
@@ -384,47 +492,62 @@ def emit():
             first = False
     h.append("}")
     h.append("")
+    h.append("// of tile t: the lane's running maximum, the reference maximum, the column's exp-sum over all tokens so far")
+    h.append("// (relative to the reference; the same in the column's four lanes)")
+    h.append("template <int t>")
+    h.append("__device__ __forceinline__ void read_state(float &m, float &mref, float &esum)")
+    h.append("{")
+    first = True
+    for t in range(4):
+        h.append("    %sif constexpr (t == %d)" % ("" if first else "else ", t))
+        h.append('        asm volatile("v_mov_b32_e32 %%0, v%d\\n v_mov_b32_e32 %%1, v%d\\n v_accvgpr_read_b32 %%2, a%d\\n" : "=v"(m), "=v"(mref), "=v"(esum));'
+                 % (M(t), MREF(t), ESUM(t)))
+        first = False
+    h.append("}")
+    h.append("")
     h.append("// matrix results may be read by other instructions 8 issue slots after the product at the earliest")
     h.append('__device__ __forceinline__ void settle() { asm volatile("s_nop 7\\n s_nop 7" ::: ); }')
     h.append("")
-    for tiles in (2, 4):
-        h.append("// requests the V and K rows of a chunk into buffer `buf` (the first two chunks of a wavefront, or when a")
-        h.append("// chunk slot is skipped), in the order the chunk statements for %d tiles request them" % tiles)
-        h.append("template <int buf>")
-        h.append("__device__ __forceinline__ void issue_loads_%d(const NextLoads &nl, const LaneConstants &lc)" % tiles)
-        h.append("{")
-        for b in (0, 1):
-            h.append("    %sif constexpr (buf == %d)" % ("" if b == 0 else "else ", b))
-            h.append("    asm volatile(")
-            h.append(c_string(loads(tiles, b)))
-            h.append("        :: " + LOAD_OPS + ");")
-        h.append("}")
-        h.append("")
+    h.append("// Requests the V and K rows of a chunk and builds its V^T operands: before a wavefront's first chunk, and in place")
+    h.append("// of the chunk statement for a chunk slot without valid rows (`nl` then describes the chunk after it).")
+    h.append("// NT: non-temporal loads (rows that no other wavefront reads).")
+    h.append("template <bool NT>")
+    h.append("__device__ __forceinline__ void request_chunk(const NextLoads &nl, const LaneConstants &lc)")
+    h.append("{")
+    h.append("    const uint32_t sel_lo = 0x05040100u, sel_hi = 0x07060302u;")
+    for nt in (True, False):
+        h.append("    %sif constexpr (%sNT)" % ("" if nt else "else ", "" if nt else "!"))
+        h.append("    asm volatile(")
+        h.append(c_string(check(request_body(" nt" if nt else ""))))
+        h.append("        :: " + LOAD_OPS)
+        h.append('        : "vcc", "scc");')
+    h.append("}")
+    h.append("")
     for tiles in (2, 4):
         for masked in (False, True):
             name = "chunk_%d%s" % (tiles, "_masked" if masked else "")
-            h.append("// One 32-token chunk (its rows in buffer `buf`) for %d column tiles%s: scores, maxima, (rarely) the rescale,"
-                     % (tiles, ", some rows masked" if masked else ""))
-            h.append("// weights, V^T.P^T; requests the rows of the chunk after the next into `buf`.  m: lane's running maximum; mref:")
-            h.append("// reference maximum; nmu: -mref, or 0 while mref = -inf; e: lane's exp-sum.")
-            args = ("float (&m)[%d], float (&mref)[%d], float (&nmu)[%d], float (&e)[%d], float c2, const NextLoads &nl, const LaneConstants &lc, uint32_t bp16, uint32_t bp32"
-                    % (tiles, tiles, tiles, tiles))
+            h.append("// One 32-token chunk for %d column tiles%s: scores, maxima, (rarely) the rescale, weights, V^T.P^T; requests"
+                     % (tiles, ", some rows masked (rs = rows the lane's column sees - 4 * lane group)" if masked else ""))
+            h.append("// the rows of the next chunk (`nl`) and builds its V^T operands.")
+            args = "float c2, const NextLoads &nl, const LaneConstants &lc, uint32_t bp16, uint32_t bp32"
             if masked:
                 args += ", const int (&rs)[%d]" % tiles
-            h.append("template <int buf>")
+            h.append("template <bool NT>")
             h.append("__device__ __forceinline__ void %s(%s)" % (name, args))
             h.append("{")
             h.append("    const uint32_t sel_lo = 0x05040100u, sel_hi = 0x07060302u;")
             h.append("    const uint32_t neg_lo = 0x0000bf80u, neg_hi = 0xbf800000u;  // bf16 pairs (-1, 0) and (0, -1)")
-            ops = '[c2] "s"(c2), [sel_lo] "s"(sel_lo), [sel_hi] "s"(sel_hi), [neg_lo] "s"(neg_lo), [neg_hi] "s"(neg_hi), [bp16] "v"(bp16), [bp32] "v"(bp32), ' + LOAD_OPS
+            ops = '[c2] "s"(c2), [neg_lo] "s"(neg_lo), [neg_hi] "s"(neg_hi), [bp16] "v"(bp16), [bp32] "v"(bp32), ' + LOAD_OPS
             if masked:
                 ops += ", " + ', '.join('[rs%d] "v"(rs[%d])' % (t, t) for t in range(tiles))
-            for b in (0, 1):
-                h.append("    %sif constexpr (buf == %d)" % ("" if b == 0 else "else ", b))
+            for nt in (True, False):
+                if tiles == 2 and not nt:
+                    h.append("    else static_assert(NT, \"two tiles: non-temporal loads only\");")
+                    continue
+                h.append("    %sif constexpr (%sNT)" % ("" if nt else "else ", "" if nt else "!"))
                 h.append("    asm volatile(")
-                h.append(c_string(body(tiles, masked, b)))
-                h.append("        : " + state_ops(tiles))
-                h.append("        : " + ops)
+                h.append(c_string(check(body(tiles, masked, " nt" if nt else ""))))
+                h.append("        :: " + ops)
                 h.append('        : "vcc", "scc", "s100", "s101");')
             h.append("}")
             h.append("")

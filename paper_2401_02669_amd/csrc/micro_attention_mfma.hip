@@ -18,7 +18,8 @@
 //
 // The columns of a work item are (query token, q-head) pairs of the kv-head's group: q-heads for
 // plain decode, query tokens x q-heads in the multi-query form, where each column also has its own
-// causal limit.  A work item serves TILES (1, 2 or 4) tiles of 16 columns from one K/V read.  Columns
+// causal limit.  A work item serves TILES (1, 2 or 4) tiles of 16 columns from one K/V read (bf16 with more than
+// one tile has a kernel of its own, micro_attention_mfma_tiles.hip; here more than one tile is IEEE half).  Columns
 // past the group carry q = 0 and are never written.
 #include <hip/hip_runtime.h>
 
@@ -476,10 +477,12 @@ hipError_t launch_tiles(const MicroParams &p, int grid, hipStream_t stream)
         return hipErrorInvalidValue;
     else if (p.head_tile == kHeadTile)
         hipLaunchKernelGGL((micro_attention_mfma_kernel<1, F16, false>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+    else if (!F16)
+        return hipErrorInvalidValue;  // bf16 with more than one column tile: micro_attention_mfma_tiles.hip
     else if (p.head_tile == 2 * kHeadTile)
-        hipLaunchKernelGGL((micro_attention_mfma_kernel<2, F16, false>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+        hipLaunchKernelGGL((micro_attention_mfma_kernel<2, true, false>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     else if (p.head_tile == 4 * kHeadTile)
-        hipLaunchKernelGGL((micro_attention_mfma_kernel<4, F16, false>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+        hipLaunchKernelGGL((micro_attention_mfma_kernel<4, true, false>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

@@ -151,3 +151,35 @@ def test_partials_of_many_columns_report_the_true_maximum():
     np.testing.assert_allclose(pe[live], e[live], rtol=3e-4)
     num = np.linalg.norm(po[live] - MA[live], axis=1)
     assert np.all(num <= 1e-3 * np.linalg.norm(MA[live], axis=1) + 1e-12)
+
+
+@pytest.mark.parametrize("Hq,Hkv,n", [(64, 1, 1), (8, 2, 16), (16, 1, 8), (8, 1, 16), (32, 1, 1), (8, 2, 6), (16, 2, 20)])
+def test_first_chunk_is_a_partly_visible_one(Hq, Hkv, n):
+    # requests so short that the first chunk a wavefront sees is one with masked rows (the reference maximum is set
+    # and rows are masked in the same chunk), for 32, 64 and 128 columns per work item
+    lens = [31, 33, 1, 64, 95, 127, 4101]
+    w = make(lens, n, Hq, Hkv, T=64, seed=100 + Hq + n)
+    print("case short requests n=%d Hq=%d Hkv=%d" % (n, Hq, Hkv), flush=True)
+    ref_out, ref_lse = ref_of(w)
+    for bps in (0, 1):
+        plan, fused, two_step, _ = run_both(w, blocks_per_split=bps)
+        plan.close()
+        for (out, lse), what in ((fused, "fused"), (two_step, "two-step")):
+            assert_parity(out.reshape(ref_out.shape), lse.reshape(ref_lse.shape), ref_out, ref_lse, "bf16", "%s bps=%d" % (what, bps))
+
+
+@pytest.mark.parametrize("Hq,Hkv,n,dtype,kernel", [(8, 8, 1, "bf16", da.DA_KERNEL_AUTO), (32, 1, 1, "bf16", da.DA_KERNEL_AUTO),
+                                                   (8, 2, 16, "bf16", da.DA_KERNEL_AUTO), (8, 1, 16, "bf16", da.DA_KERNEL_AUTO),
+                                                   (8, 2, 3, "bf16", da.DA_KERNEL_VALU), (8, 1, 2, "f32", da.DA_KERNEL_AUTO),
+                                                   (4, 4, 1, "f32", da.DA_KERNEL_AUTO)])
+def test_negative_score_scale(Hq, Hkv, n, dtype, kernel):
+    # scores are scale * q.k for any sign of the scale: the largest score then belongs to the most negative product
+    lens = [700, 0, 1, 33, 64, 2049]
+    w = make(lens, n, Hq, Hkv, T=64, dtype=dtype, seed=7 + n)
+    w["scale"] = -0.11
+    print("case negative scale n=%d Hq=%d Hkv=%d %s kernel=%d" % (n, Hq, Hkv, dtype, kernel), flush=True)
+    ref_out, ref_lse = ref_of(w)
+    plan, fused, two_step, _ = run_both(w, kernel=kernel)
+    plan.close()
+    for (out, lse), what in ((fused, "fused"), (two_step, "two-step")):
+        assert_parity(out.reshape(ref_out.shape), lse.reshape(ref_lse.shape), ref_out, ref_lse, dtype, what)

@@ -288,21 +288,25 @@ def interleave(major, minor, per):
 
 def resolve_waits(stream, old_queue):
     """Turns need / load markers into s_waitcnt vmcnt(n).  Vector loads return in order; when the stream starts, the
-    loads named in old_queue (oldest first) may all be outstanding.  A need means the newest load of that name."""
+    loads named in old_queue (oldest first) may all be outstanding.  A need means the newest load of that name;
+    needs that follow one another become one wait."""
     queue = list(old_queue)
     done = 0                  # this many from the front are known to have returned
+    want = 0                  # ... and this many must have before the next instruction
     out = []
     for x in stream:
+        if isinstance(x, tuple) and x[0] == "need":
+            want = max(want, len(queue) - queue[::-1].index(x[1]))
+            continue
+        if want > done:
+            out.append("s_waitcnt vmcnt(%d)" % (len(queue) - want))
+            done = want
         if isinstance(x, str):
             out.append(x)
-        elif x[0] == "load":
+        else:
             out.append(x[2])
             queue.append(x[1])
-        else:
-            pos = len(queue) - 1 - queue[::-1].index(x[1])
-            if pos >= done:
-                out.append("s_waitcnt vmcnt(%d)" % (len(queue) - 1 - pos))
-                done = pos + 1
+    assert want <= done
     return out, queue[done:]
 
 

@@ -399,7 +399,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="all",
                     help="all (c2_7b c3_70b c4_2m c5_mixed + c1_tiny), names of synth.WORKLOADS (comma-separated), ctx_sweep, short_sweep")
     ap.add_argument("--len-div", type=int, default=1, help="divide every length (debug only; result is not the named workload)")

@@ -1,7 +1,8 @@
 """Oracle for the cluster-level KV placement step: performance model and greedy scheduler.
 
-TEST INFRASTRUCTURE ONLY.  Plain Python floats (fp64) and loops, written from Section 5.3 (Eq. 5, 6, 7 and
-Algorithm 1) in the paper's order and notation; nothing here is shared with the C++ implementation.
+TEST INFRASTRUCTURE ONLY.  Plain Python floats (fp64), written from Section 5.2 / 5.3 (Eq. 5, 6, 7 and the greedy
+rule of Algorithm 1, stated here as a definition: roles, the request that gives blocks, the admissible block counts,
+the argmax, the order of offers) in the paper's notation; nothing here is shared with the C++ implementation.
 
 Notation: beta = batch size of an instance, S^r = length of request r in tokens, g = attention rate in tokens per
 second (a constant, Section 5.3), T^natn(beta) = W(beta) / f(beta) = measured time of the non-attention part of one
@@ -151,40 +152,64 @@ def apply_move(model, debtor, r, creditor, k):
     creditor.hosted_blocks += k
 
 
+def is_creditor(model, inst, u_thres):
+    """Section 5.2: spare memory (utilisation at most U^thres) and nothing of its own placed elsewhere."""
+    return utilisation(model, inst) <= u_thres and remote_blocks(inst) == 0
+
+
+def is_debtor(model, inst, beta_thres, u_thres):
+    """Section 5.2: a small batch (at most beta^thres) on an instance that is no creditor, has a request to give
+    blocks from and hosts nothing for others."""
+    return (batch(inst) <= beta_thres and not is_creditor(model, inst, u_thres) and len(inst.req_tokens) > 0
+            and inst.hosted_blocks == 0)
+
+
+def longest_request(inst):
+    """The request a debtor gives blocks from; the lower index among equally long ones."""
+    return min(range(len(inst.req_tokens)), key=lambda r: (-inst.req_tokens[r], r))
+
+
+def movable_blocks(model, debtor, r, creditor):
+    """The block counts k the rule may choose from: 0 up to what the creditor has free, and never the request's
+    last local block (new tokens are appended there)."""
+    local = blocks_of(model, debtor.req_tokens[r]) - debtor.req_remote_blocks[r]
+    free = creditor.capacity_blocks - used_blocks(model, creditor)
+    return range(0, max(0, min(local, free + 1)))
+
+
+def blocks_to_move(model, debtor, r, creditor):
+    """The greedy choice: the k whose estimate for the pair (Eq. 6 for both, summed as in Eq. 7) is largest; the
+    smallest such k, so that "nothing gained" is 0."""
+    ks = movable_blocks(model, debtor, r, creditor)
+    return max(ks, key=lambda k: (pair_estimate(model, debtor, creditor, k), -k)) if len(ks) else 0
+
+
 def schedule(model, instances, beta_thres, u_thres):
-    """Algorithm 1.  Returns (moves, instances_after); a move is (debtor, request, creditor, blocks)."""
+    """The placement rule of Section 5.3 stated as a definition.  Returns (moves, instances_after); a move is
+    (debtor, request, creditor, blocks).
+
+    Debtors are served in order of batch size.  A debtor offers blocks of its longest request to the creditors one
+    at a time, always to the least utilised creditor it has not offered to yet (utilisations as they stand then);
+    the number of blocks that creditor takes is blocks_to_move; the first creditor that takes none ends the
+    debtor's turn."""
     inst = [i.copy() for i in instances]
-    M = len(inst)
-    is_creditor = [utilisation(model, inst[i]) <= u_thres and remote_blocks(inst[i]) == 0 for i in range(M)]
-    debtors = [i for i in range(M)
-               if batch(inst[i]) <= beta_thres and not is_creditor[i] and len(inst[i].req_tokens) > 0
-               and inst[i].hosted_blocks == 0]
-    debtors.sort(key=lambda i: (batch(inst[i]), i))
-    creditors = [i for i in range(M) if is_creditor[i]]
+    everyone = range(len(inst))
+    creditors = [c for c in everyone if is_creditor(model, inst[c], u_thres)]
+    debtors = sorted((d for d in everyone if is_debtor(model, inst[d], beta_thres, u_thres)), key=lambda d: (batch(inst[d]), d))
     moves = []
+
+    def offer(d, r, asked):
+        open_to = [c for c in creditors if c not in asked]
+        if not open_to:
+            return
+        c = min(open_to, key=lambda x: (utilisation(model, inst[x]), x))
+        k = blocks_to_move(model, inst[d], r, inst[c])
+        if k == 0:
+            return
+        apply_move(model, inst[d], r, inst[c], k)
+        moves.append((d, r, c, k))
+        offer(d, r, asked | {c})
+
     for d in debtors:
-        D = inst[d]
-        r = max(range(len(D.req_tokens)), key=lambda x: (D.req_tokens[x], -x))
-        block_max = blocks_of(model, D.req_tokens[r]) - D.req_remote_blocks[r]
-        tried = set()
-        while True:
-            order = sorted((c for c in creditors if c not in tried), key=lambda c: (utilisation(model, inst[c]), c))
-            if not order:
-                break
-            c = order[0]
-            tried.add(c)
-            C = inst[c]
-            free_c = C.capacity_blocks - used_blocks(model, C)
-            best_k, best_perf = 0, None
-            for k in range(0, block_max):
-                if k > free_c:
-                    break
-                perf = pair_estimate(model, D, C, k)
-                if best_perf is None or perf > best_perf:
-                    best_k, best_perf = k, perf
-            if best_k <= 0:
-                break
-            apply_move(model, D, r, C, best_k)
-            moves.append((d, r, c, best_k))
-            block_max -= best_k
+        offer(d, longest_request(inst[d]), frozenset())
     return moves, inst

@@ -132,3 +132,29 @@ def test_append_and_move_half_rows_bit_exact():
                    torch.as_tensor([2, 4, 0], dtype=torch.int32, device=DEV))
     torch.cuda.synchronize()
     assert np.array_equal(bits(kd).view(np.uint16), hk.view(np.uint16)) and np.array_equal(bits(vd).view(np.uint16), hv.view(np.uint16))
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,n", [("f16", 8, 2, 2), ("f16", 16, 1, 3), ("bf16", 8, 2, 2), ("bf16", 8, 1, 8)])
+def test_chunk_invisible_to_a_column_with_strongly_negative_scores(dtype, Hq, Hkv, n):
+    # every score is about -150: a column's running maximum is far below the point where exp2(-maximum) overflows.
+    # Lengths 32 k + 1 put the newest token alone in the last chunk, which the earlier query tokens may not see at
+    # all: that chunk has to join their sums with weight 0, not with 0 * inf.
+    lens = [33, 65, 1, 97, 2049, 32 * 7 + n - 1]
+    w = synth.make(synth.recipe("c5_mixed", B=len(lens), Hq=Hq, Hkv=Hkv, T=64, dtype=dtype, lens=lens), DEV)
+    tdt = torch.float16 if dtype == "f16" else torch.bfloat16
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    w["q"] = torch.ones((len(lens), n, Hq, 128), device=DEV).to(tdt)
+    k = w["k_pool"]
+    noise = torch.randn(k.shape, device=DEV, generator=gen) * 0.05 - 1.2
+    w["k_pool"].copy_(torch.where(torch.isnan(k.float()), k.float(), noise).to(tdt))  # the poison in unused slots stays
+    w["scale"] = 1.0
+    ref_out, ref_lse = oracle.attention(bits(w["q"]), bits(w["k_pool"]), bits(w["v_pool"]), w["block_table_host"],
+                                        w["seq_lens_host"], w["T"], w["scale"], n_threads=16)
+    assert np.all(np.isfinite(ref_out)) and ref_lse[np.isfinite(ref_lse)].max() < -100
+    for kernel in (da.DA_KERNEL_AUTO, da.DA_KERNEL_VALU):
+        plan = da.Plan(da.make_problem(w["q"], w["k_pool"], w["block_table"], w["scale"]), w["seq_lens_host"].tolist(), kernel=kernel)
+        out, lse = plan.attention(w["q"], w["k_pool"], w["v_pool"], w["block_table"], w["seq_lens"])
+        torch.cuda.synchronize()
+        plan.close()
+        assert_parity(out.cpu().numpy(), lse.cpu().numpy(), ref_out, ref_lse, dtype, "%s kernel=%d" % (dtype, kernel))

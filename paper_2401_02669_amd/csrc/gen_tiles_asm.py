@@ -333,8 +333,12 @@ def request_body(nt):
     return offsets_prologue() + ins + offsets_epilogue() + ["s_branch 29f"] + offsets_out_of_line() + ["29:"]
 
 
-def body(tiles, masked, nt):
-    ins = offsets_prologue()
+RUN_KB, RUN_VB, RUN_N = "s[96:97]", "s[98:99]", "s95"  # scalar registers of a run statement: row pointers, chunks left
+
+
+def body(tiles, masked, nt, run=False):
+    """One chunk; with run, a loop over chunks whose successors are all full and lie `step` bytes apart."""
+    ins = ["60:"] if run else offsets_prologue()
     # ---- V rows of the next chunk; K.Q^T of tile 0 ------------------------------------------------------------
     s = [v_load(j, nt) for j in range(8)]
     for j in K_ORDER:
@@ -353,7 +357,14 @@ def body(tiles, masked, nt):
     s += rest[:head] + interleave(rest[head:], side, 3 if tiles == 4 else 8)
     first, queue = resolve_waits(s, OLD_K)
     assert queue[-8:] == OLD_K, queue
-    ins += first + offsets_epilogue()
+    ins += first
+    if run:   # all requests of the iteration are out: on to the rows of the next one
+        assert not masked
+        for pair in (RUN_KB, RUN_VB):
+            lo, hi = pair[2:pair.index(":")], pair[pair.index(":") + 1:-1]
+            ins += ["s_add_u32 s%s, s%s, %%[step]" % (lo, lo), "s_addc_u32 s%s, s%s, 0" % (hi, hi)]
+    else:
+        ins += offsets_epilogue()
     # ---- tile after tile: V^T.P^T under the maxima / weights of the tiles after it ------------------------------
     for t in range(tiles):
         pv, free_after = pv_mfmas(t, t % 2)
@@ -385,8 +396,13 @@ def body(tiles, masked, nt):
     for u in range(1, tiles):
         ins += rescale_tile(u, "3%d" % (4 + u))
     ins += ["s_branch 33b"]
-    ins += offsets_out_of_line()
+    if not run:
+        ins += offsets_out_of_line()
     ins += ["39:"]
+    if run:
+        ins += ["s_sub_u32 %s, %s, 1" % (RUN_N, RUN_N), "s_cmp_lg_u32 %s, 0" % RUN_N, "s_cbranch_scc1 60b"]
+        ins = [i.replace("%[kbase]", RUN_KB).replace("%[vbase]", RUN_VB) for i in ins]
+        ins = ["s_mov_b64 %s, %%[kbase]" % RUN_KB, "s_mov_b64 %s, %%[vbase]" % RUN_VB, "s_mov_b32 %s, %%[n]" % RUN_N] + ins
     return ins
 
 
@@ -555,6 +571,27 @@ def emit():
                 h.append('        : "vcc", "scc", "s100", "s101");')
             h.append("}")
             h.append("")
+    for tiles in (2, 4):
+        h.append("// n chunks of 32 tokens one after the other for %d column tiles, none with a masked row; iteration i requests" % tiles)
+        h.append("// the rows `nl` + i * step bytes, all of them full chunks (the rows of the chunk after the one it processes).")
+        h.append("template <bool NT>")
+        h.append("__device__ __forceinline__ void chunk_%d_run(float c2, const NextLoads &nl, const LaneConstants &lc, uint32_t bp16, uint32_t bp32, uint32_t n, uint32_t step)" % tiles)
+        h.append("{")
+        h.append("    const uint32_t sel_lo = 0x05040100u, sel_hi = 0x07060302u;")
+        h.append("    const uint32_t neg_lo = 0x0000bf80u, neg_hi = 0xbf800000u;  // bf16 pairs (-1, 0) and (0, -1)")
+        ops = ('[c2] "s"(c2), [neg_lo] "s"(neg_lo), [neg_hi] "s"(neg_hi), [bp16] "v"(bp16), [bp32] "v"(bp32), [n] "s"(n), [step] "s"(step), '
+               '[vbase] "s"(nl.vb), [kbase] "s"(nl.kb), [sel_lo] "s"(sel_lo), [sel_hi] "s"(sel_hi)')
+        for nt in (True, False):
+            if tiles == 2 and not nt:
+                h.append("    else static_assert(NT, \"two tiles: non-temporal loads only\");")
+                continue
+            h.append("    %sif constexpr (%sNT)" % ("" if nt else "else ", "" if nt else "!"))
+            h.append("    asm volatile(")
+            h.append(c_string(check(body(tiles, False, " nt" if nt else "", run=True))))
+            h.append("        :: " + ops)
+            h.append('        : "vcc", "scc", "s100", "s101", "s95", "s96", "s97", "s98", "s99");')
+        h.append("}")
+        h.append("")
     h.append("}  // namespace tiles_asm")
     h.append("}  // namespace da")
     return "\n".join(h) + "\n"

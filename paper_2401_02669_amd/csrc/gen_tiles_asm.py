@@ -22,14 +22,15 @@ over a fixed register map:
     v[236:245]  the lane's byte offsets of its 8 V loads and 2 groups of K loads inside a full chunk
     v[246:247]  clamps for a chunk whose last rows are not valid
 
-Order of a chunk statement (chunk i; the K rows of i were requested by the statement before, its V^T operands built
-there):
-    request the V rows of chunk i+1
-    K.Q^T: tile 0 first, then the other tiles K register by K register, each register requested again (chunk i+1)
-           after its last product; under these products: maximum, (rarely) rescale and weights of tile 0
-    tile after tile: V^T.P^T of tile t (and the ones row) under the maxima / weights of the tiles after it
-    under the last tile's products: the V^T operands of chunk i+1 from its V rows
-so that matrix and vector instructions alternate nearly everywhere.
+Order of a chunk statement (chunk i; the K rows of i were requested by the statement before, the V^T operands of its
+dimension groups 0 and 1 built there):
+    K.Q^T of tile 0; behind its products the V^T operands of groups 2 and 3, then the requests for the V rows of i+1
+    K.Q^T of the other tiles, K register by K register, each register requested again (chunk i+1) after its last
+           product; behind them: maximum, (rarely) rescale and the weights' high parts of tile 0
+    tile after tile: V^T.P^T of tile t with the high parts of its weights, then with the low parts (and the ones row);
+           behind them: the low parts of tile t's weights, (t = 0: maxima and rescale of all other tiles,) the
+           weights' high parts of tile t+1; behind the last tile's products the V^T operands of groups 0 and 1 of i+1
+How many vector instructions go behind one product follows from measured issue costs (see interleave).
 
 Run `python gen_tiles_asm.py` after changing it; the header it writes is committed beside it.
 """
@@ -190,9 +191,8 @@ def max_tile(t, d):
             "v_sub_f32_e32 v%d, v%d, v%d" % (d, M(t), MREF(t))]
 
 
-def weights_tile(t, b):
-    """exp2(score * c2 - reference), split into bf16 high and low parts, for tile t into weight buffer b.
-    Temporaries 0..7 only, so that the maxima (12..15) may run beside it."""
+def weights_head(t, b):
+    """exp2(score * c2 - reference) for tile t (temporaries 0..7) and its bf16 high parts (weight buffer b)."""
     out = []
     for i in range(8):
         out.append("v_fma_f32 v%d, v%d, %%[c2], v%d" % (T(i), S(t, i), NMU(t)))
@@ -200,27 +200,42 @@ def weights_tile(t, b):
         out.append("v_exp_f32_e32 v%d, v%d" % (T(i), T(i)))
     for k in range(4):
         out.append("v_cvt_pk_bf16_f32 v%d, v%d, v%d" % (PH(b) + k, T(2 * k), T(2 * k + 1)))
-    # what the high parts leave: w - high, one dot product per weight (high pair . (-1, 0) + w, high pair . (0, -1) + w)
+    return out + ["s_nop 1"]   # the tile's products may follow at once: they read a register two slots after its write
+
+
+def weights_low(b):
+    """What the high parts leave of the weights in temporaries 0..7: w - high, with the high parts widened again by
+    a shift / a mask (temporaries 8..11), as bf16.  (A bf16 dot product would do it in one instruction per weight,
+    but it runs on the matrix pipe and waits for every product in flight.)"""
+    out = []
     for k in range(4):
-        out.append("v_dot2_f32_bf16 v%d, v%d, %%[neg_lo], v%d" % (T(2 * k), PH(b) + k, T(2 * k)))
-        out.append("v_dot2_f32_bf16 v%d, v%d, %%[neg_hi], v%d" % (T(2 * k + 1), PH(b) + k, T(2 * k + 1)))
+        e, o = T(8 + 2 * (k % 2)), T(9 + 2 * (k % 2))
+        out.append("v_lshlrev_b32_e32 v%d, 16, v%d" % (e, PH(b) + k))
+        out.append("v_and_b32_e32 v%d, 0xffff0000, v%d" % (o, PH(b) + k))
+        out.append("v_sub_f32_e32 v%d, v%d, v%d" % (T(2 * k), T(2 * k), e))
+        out.append("v_sub_f32_e32 v%d, v%d, v%d" % (T(2 * k + 1), T(2 * k + 1), o))
     for k in range(4):
+        if k == 3:
+            out.append(("mark", "low%d" % b))   # travels with the instruction after it: the last one
         out.append("v_cvt_pk_bf16_f32 v%d, v%d, v%d" % (PL(b) + k, T(2 * k), T(2 * k + 1)))
     return out
 
 
 def pv_mfmas(t, b):
-    """O^T += V^T . P^T of tile t (high and low weights) and the ones row, dimension group by dimension group.
-    Returns the products and, per group w, after how many of them the group's V^T operands may be overwritten."""
+    """O^T += V^T . P^T of tile t and the ones row: the products with the high parts of the weights, then (once the
+    low parts are there) those with the low parts.  Returns the products and, per dimension group w, after how many
+    of them the group's V^T operands may be overwritten."""
     out = ["%s %s, %s, %s, %s" % (MFMA, a4(ESUM(t)), a4(ONES), v4(PH(b)), a4(ESUM(t)))]
+    for w in range(4):
+        out.append("%s %s, %s, %s, %s" % (MFMA, a4(ACC(t, 2 * w)), v4(VE(w)), v4(PH(b)), a4(ACC(t, 2 * w))))
+        out.append("%s %s, %s, %s, %s" % (MFMA, a4(ACC(t, 2 * w + 1)), v4(VO(w)), v4(PH(b)), a4(ACC(t, 2 * w + 1))))
+    out.append(("wait", "low%d" % b))
+    out.append("%s %s, %s, %s, %s" % (MFMA, a4(ESUM(t)), a4(ONES), v4(PL(b)), a4(ESUM(t))))
     free_after = {}
     for w in range(4):
-        for p in (PH(b), PL(b)):
-            out.append("%s %s, %s, %s, %s" % (MFMA, a4(ACC(t, 2 * w)), v4(VE(w)), v4(p), a4(ACC(t, 2 * w))))
-            out.append("%s %s, %s, %s, %s" % (MFMA, a4(ACC(t, 2 * w + 1)), v4(VO(w)), v4(p), a4(ACC(t, 2 * w + 1))))
-        if w == 0:
-            out.append("%s %s, %s, %s, %s" % (MFMA, a4(ESUM(t)), a4(ONES), v4(PL(b)), a4(ESUM(t))))
-        free_after[w] = len(out)
+        out.append("%s %s, %s, %s, %s" % (MFMA, a4(ACC(t, 2 * w)), v4(VE(w)), v4(PL(b)), a4(ACC(t, 2 * w))))
+        out.append("%s %s, %s, %s, %s" % (MFMA, a4(ACC(t, 2 * w + 1)), v4(VO(w)), v4(PL(b)), a4(ACC(t, 2 * w + 1))))
+        free_after[w] = 10 + 2 * (w + 1)   # products issued by then
     return out, free_after
 
 
@@ -257,48 +272,112 @@ def rescale_tile(t, label):
 
 # ---------------------------------------------------------------------------------------------- streams
 
-def interleave(major, minor, per):
-    """major[0], `per` of minor, major[1], ... ; what is left of either stream follows.  Markers (tuples) travel with
-    the instruction after them, a label with the instruction before it (a branch out of the stream comes back to
-    the label right behind it: nothing may come between the two); neither counts."""
-    def units(stream):
-        out, cur = [], []
-        for n, x in enumerate(stream):
-            cur.append(x)
-            is_instr = isinstance(x, str) and not x.endswith(":")
-            label_next = n + 1 < len(stream) and isinstance(stream[n + 1], str) and stream[n + 1].endswith(":")
-            if (is_instr or (isinstance(x, str) and x.endswith(":"))) and not label_next and any(
-                    isinstance(y, str) and not y.endswith(":") for y in cur):
-                out.append(cur)
-                cur = []
-        if cur:
+# Issue cost of an instruction in cycles, measured on one wavefront per SIMD: a vector instruction 4.55 (exp2 8.1),
+# a scalar one 4.05; a matrix product occupies its pipe for 16 and the issue for 6.6 of them, so that what is issued
+# beside it is free up to about 9.4 cycles per product and delays the next product beyond that.
+SHADOW, OVERDRAFT = 9.4, 1.0
+
+
+def issue_cost(x):
+    if isinstance(x, tuple) and x[0] == "load":
+        return 8.0
+    if not isinstance(x, str) or x.endswith(":"):
+        return 0.0
+    op = x.split()[0]
+    if op == "s_nop":
+        return max(4.05, float(x.split()[1]) + 1.0)
+    if op.startswith("v_exp"):
+        return 8.1
+    if op.startswith("ds_") or op.startswith("global_"):
+        return 8.0
+    return 4.55 if op.startswith("v_") else 4.05
+
+
+def units(stream):
+    """Markers (tuples) travel with the instruction after them, a label with the instruction before it (a branch
+    out of the stream comes back to the label right behind it: nothing may come between the two)."""
+    def instr(y):   # a load is an instruction that resolve_waits still has to see
+        return (isinstance(y, str) and not y.endswith(":")) or (isinstance(y, tuple) and y[0] == "load")
+    out, cur = [], []
+    for n, x in enumerate(stream):
+        cur.append(x)
+        label_next = n + 1 < len(stream) and isinstance(stream[n + 1], str) and stream[n + 1].endswith(":")
+        if (instr(x) or (isinstance(x, str) and x.endswith(":"))) and not label_next and any(instr(y) for y in cur):
             out.append(cur)
-        return out
+            cur = []
+    if cur:
+        out.append(cur)
+    return out
+
+
+def interleave(major, minor):
+    """The minor stream in the shadow of the major stream's matrix products: after each product as many of its
+    instructions as the product's 16 cycles leave room for; what is left of either stream follows.
+    ("mark", x) in the minor stream and ("wait", x) in the major one: the major stream goes on past the wait only
+    when the minor one has passed the mark (and two more issue slots: a matrix product may read a register two
+    slots after a vector instruction wrote it).  ("after", n) in the minor stream: not before n products of the
+    major stream are out."""
     a, b = units(major), units(minor)
-    out, k = [], 0
+    out, k, products, passed, since = [], 0, 0, set(), 99
+
+    def emit_minor():
+        nonlocal k, since
+        for x in b[k]:
+            if isinstance(x, tuple) and x[0] == "mark":
+                passed.add(x[1])
+                since = -1   # the marked instruction comes next
+            elif not (isinstance(x, tuple) and x[0] == "after"):
+                out.append(x)
+                if (isinstance(x, str) and not x.endswith(":")) or (isinstance(x, tuple) and x[0] == "load"):
+                    since += 1
+        k += 1
+
+    def blocked():
+        return any(isinstance(x, tuple) and x[0] == "after" and products < x[1] for x in b[k])
+
     for u in a:
-        out += u
-        for v in b[k:k + per]:
-            out += v
-        k += per
-    for v in b[k:]:
-        out += v
+        for x in u:
+            if isinstance(x, tuple) and x[0] == "wait":
+                while x[1] not in passed:
+                    assert k < len(b) and not blocked(), x
+                    emit_minor()
+                if since < 2:
+                    out.append("s_nop %d" % (1 - since))   # 2 - since issue slots
+                    since = 2
+            else:
+                out.append(x)
+                if isinstance(x, str) and not x.endswith(":"):
+                    since += 1
+        if not any(isinstance(x, str) and x.startswith("v_mfma") for x in u):
+            continue
+        products += 1
+        room = SHADOW
+        while k < len(b) and not blocked():
+            c = sum(issue_cost(x) for x in b[k])
+            if c > room + OVERDRAFT:
+                break
+            emit_minor()
+            room -= c
+    while k < len(b):
+        emit_minor()
     return out
 
 
 def resolve_waits(stream, old_queue):
     """Turns need / load markers into s_waitcnt vmcnt(n).  Vector loads return in order; when the stream starts, the
-    loads named in old_queue (oldest first) may all be outstanding.  A need means the newest load of that name;
-    needs that follow one another become one wait."""
+    loads named in old_queue (oldest first) may all be outstanding.  A need means the newest load of that name (none
+    if it is not among those that may be outstanding); needs that follow one another become one wait."""
     queue = list(old_queue)
     done = 0                  # this many from the front are known to have returned
     want = 0                  # ... and this many must have before the next instruction
     out = []
     for x in stream:
         if isinstance(x, tuple) and x[0] == "need":
-            want = max(want, len(queue) - queue[::-1].index(x[1]))
+            if x[1] in queue:   # otherwise it has come back long ago
+                want = max(want, len(queue) - queue[::-1].index(x[1]))
             continue
         if want > done:
+            assert len(queue) - want <= 63
             out.append("s_waitcnt vmcnt(%d)" % (len(queue) - want))
             done = want
         if isinstance(x, str):
@@ -323,13 +402,20 @@ def offsets_out_of_line():
     return ["20:"] + clamp_offsets() + ["s_branch 21b", "22:"] + set_offsets() + ["s_branch 23b"]
 
 
+def still_out(queue):
+    """What a statement leaves outstanding must be what the next one assumes: K loads only, the newest ones."""
+    assert queue == OLD_K[len(OLD_K) - len(queue):], queue
+    return True
+
+
 def request_body(nt):
-    """All 16 loads of a chunk and its V^T operands."""
-    s = [v_load(j, nt) for j in range(8)] + [k_load(j, nt) for j in K_ORDER]
-    for w in range(4):
-        s += perms_of_group(w)
+    """All 16 loads of a chunk and the first half of its V^T operands (the second half of those before them first,
+    as every statement does)."""
+    s = perms_of_group(2) + perms_of_group(3)
+    s += [v_load(j, nt) for j in range(8)] + [k_load(j, nt) for j in K_ORDER]
+    s += perms_of_group(0) + perms_of_group(1)
     ins, left = resolve_waits(s, OLD_K)
-    assert left[-8:] == OLD_K, left
+    assert still_out(left)
     return offsets_prologue() + ins + offsets_epilogue() + ["s_branch 29f"] + offsets_out_of_line() + ["29:"]
 
 
@@ -337,26 +423,31 @@ RUN_KB, RUN_VB, RUN_N = "s[96:97]", "s[98:99]", "s95"  # scalar registers of a r
 
 
 def body(tiles, masked, nt, run=False):
-    """One chunk; with run, a loop over chunks whose successors are all full and lie `step` bytes apart."""
+    """One chunk; with run, a loop over chunks whose successors are all full and lie `step` bytes apart.
+
+    Matrix products and vector instructions share the issue: a product needs 6.6 cycles of it and 16 of its pipe, so
+    every product should have two vector instructions (one exp2) behind it.  The products of a chunk come in the
+    order K.Q^T of tile 0, K.Q^T of the other tiles, then per tile V^T.P^T with the high parts of the weights and
+    V^T.P^T with their low parts; behind them run, in this order: the V^T operands of dimension groups 2 and 3
+    (left over from the statement before), the requests for the next V rows, maximum / rescale / weights of tile 0,
+    and per tile t: low parts of tile t's weights, (t = 0: maxima and rescale of all other tiles,) weights of tile
+    t + 1; behind the last tile's products the V^T operands of groups 0 and 1 of the next chunk."""
     ins = ["60:"] if run else offsets_prologue()
-    # ---- V rows of the next chunk; K.Q^T of tile 0 ------------------------------------------------------------
-    s = [v_load(j, nt) for j in range(8)]
+    # ---- K.Q^T: tile 0, then the other tiles K register by K register (each asked for again after its last product)
+    major = []
     for j in K_ORDER:
-        s += [("need", "K%d" % j), qk(0, j)]
-    # ---- K.Q^T of the other tiles, K register by K register, under tile 0's maximum and weights ---------------
-    rest = []
+        major += [("need", "K%d" % j), qk(0, j)]
     for j in K_ORDER:
-        rest += [qk(t, j) for t in range(1, tiles)] + [k_load(j, nt)]
-    side = ["s_nop 1"] * 2   # tile 0's last scores settle under the first products of the other tiles
+        major += [qk(t, j) for t in range(1, tiles)] + [k_load(j, nt)]
+    minor = perms_of_group(2) + perms_of_group(3)
+    minor += [v_load(j, nt) for j in range(8)]
+    minor += [("after", 10)]   # tile 0's last scores are written when two more products have gone out
     if masked:
-        side += mask_tile(0)
-    side += max_tile(0, T(14))
-    side += ["v_cmp_lt_f32_e32 vcc, 0x41800000, v%d" % T(14), "s_cbranch_vccnz 30f", "31:"]
-    side += weights_tile(0, 0)
-    head = 2 * tiles   # two K registers' worth of products and loads before the side stream starts
-    s += rest[:head] + interleave(rest[head:], side, 3 if tiles == 4 else 8)
-    first, queue = resolve_waits(s, OLD_K)
-    assert queue[-8:] == OLD_K, queue
+        minor += mask_tile(0)
+    minor += max_tile(0, T(14))
+    minor += ["v_cmp_lt_f32_e32 vcc, 0x41800000, v%d" % T(14), "s_cbranch_vccnz 30f", "31:"]
+    minor += weights_head(0, 0)
+    first, queue = resolve_waits(interleave(major, minor), OLD_K)
     ins += first
     if run:   # all requests of the iteration are out: on to the rows of the next one
         assert not masked
@@ -365,11 +456,12 @@ def body(tiles, masked, nt, run=False):
             ins += ["s_add_u32 s%s, s%s, %%[step]" % (lo, lo), "s_addc_u32 s%s, s%s, 0" % (hi, hi)]
     else:
         ins += offsets_epilogue()
-    # ---- tile after tile: V^T.P^T under the maxima / weights of the tiles after it ------------------------------
+    # ---- tile after tile: V^T.P^T; behind it the low parts of its own weights, then what the next tile needs ------
     for t in range(tiles):
         pv, free_after = pv_mfmas(t, t % 2)
+        side = weights_low(t % 2)
         if t == 0:
-            side = ["s_nop 7"]   # the last scores of the other tiles settle
+            side += [("after", 2)]   # the last scores of the other tiles are written
             for u in range(1, tiles):
                 if masked:
                     side += mask_tile(u)
@@ -377,32 +469,28 @@ def body(tiles, masked, nt, run=False):
                 if u > 1:
                     side += ["v_max_f32_e32 v%d, v%d, v%d" % (T(14), T(14), T(12))]
             side += ["v_cmp_lt_f32_e32 vcc, 0x41800000, v%d" % T(14), "s_cbranch_vccnz 32f", "33:"]
-            side += weights_tile(1, 1)
-            ins += interleave(pv, side, 3)
-        elif t + 1 < tiles:
-            ins += interleave(pv, weights_tile(t + 1, (t + 1) % 2), 2)
+        if t + 1 < tiles:
+            side += weights_head(t + 1, (t + 1) % 2)
+            ins += interleave(pv, side)
         else:
             # the last tile's products free the V^T operands group by group; the next chunk's are built behind them
-            s = pv[:free_after[0]]
-            for w in range(3):
-                s += interleave(pv[free_after[w]:free_after[w + 1]], perms_of_group(w), 2)
-            s += perms_of_group(3)
-            last, queue = resolve_waits(s, queue)
-            assert queue == OLD_K, queue
+            for w in range(2):
+                side += [("after", free_after[w])] + perms_of_group(w)
+            last, queue = resolve_waits(interleave(pv, side), queue)
             ins += last
-    ins += ["s_branch 39f"]
-    ins += ["30:"] + rescale_tile(0, "34") + ["s_branch 31b"]
-    ins += ["32:"]
+    # what is rare lies behind the stream (a taken branch costs about 70 cycles: a loop has one per iteration)
+    rare = ["30:"] + rescale_tile(0, "34") + ["s_branch 31b", "32:"]
     for u in range(1, tiles):
-        ins += rescale_tile(u, "3%d" % (4 + u))
-    ins += ["s_branch 33b"]
-    if not run:
-        ins += offsets_out_of_line()
-    ins += ["39:"]
+        rare += rescale_tile(u, "3%d" % (4 + u))
+    rare += ["s_branch 33b"]
     if run:
-        ins += ["s_sub_u32 %s, %s, 1" % (RUN_N, RUN_N), "s_cmp_lg_u32 %s, 0" % RUN_N, "s_cbranch_scc1 60b"]
+        ins += ["s_sub_u32 %s, %s, 1" % (RUN_N, RUN_N), "s_cmp_lg_u32 %s, 0" % RUN_N, "s_cbranch_scc1 60b", "s_branch 39f"]
+        ins += rare + ["39:"]
         ins = [i.replace("%[kbase]", RUN_KB).replace("%[vbase]", RUN_VB) for i in ins]
         ins = ["s_mov_b64 %s, %%[kbase]" % RUN_KB, "s_mov_b64 %s, %%[vbase]" % RUN_VB, "s_mov_b32 %s, %%[n]" % RUN_N] + ins
+    else:
+        ins += ["s_branch 39f"] + rare + offsets_out_of_line() + ["39:"]
+    assert still_out(queue)
     return ins
 
 
@@ -556,8 +644,7 @@ def emit():
             h.append("__device__ __forceinline__ void %s(%s)" % (name, args))
             h.append("{")
             h.append("    const uint32_t sel_lo = 0x05040100u, sel_hi = 0x07060302u;")
-            h.append("    const uint32_t neg_lo = 0x0000bf80u, neg_hi = 0xbf800000u;  // bf16 pairs (-1, 0) and (0, -1)")
-            ops = '[c2] "s"(c2), [neg_lo] "s"(neg_lo), [neg_hi] "s"(neg_hi), [bp16] "v"(bp16), [bp32] "v"(bp32), ' + LOAD_OPS
+            ops = '[c2] "s"(c2), [bp16] "v"(bp16), [bp32] "v"(bp32), ' + LOAD_OPS
             if masked:
                 ops += ", " + ', '.join('[rs%d] "v"(rs[%d])' % (t, t) for t in range(tiles))
             for nt in (True, False):
@@ -578,8 +665,7 @@ def emit():
         h.append("__device__ __forceinline__ void chunk_%d_run(float c2, const NextLoads &nl, const LaneConstants &lc, uint32_t bp16, uint32_t bp32, uint32_t n, uint32_t step)" % tiles)
         h.append("{")
         h.append("    const uint32_t sel_lo = 0x05040100u, sel_hi = 0x07060302u;")
-        h.append("    const uint32_t neg_lo = 0x0000bf80u, neg_hi = 0xbf800000u;  // bf16 pairs (-1, 0) and (0, -1)")
-        ops = ('[c2] "s"(c2), [neg_lo] "s"(neg_lo), [neg_hi] "s"(neg_hi), [bp16] "v"(bp16), [bp32] "v"(bp32), [n] "s"(n), [step] "s"(step), '
+        ops = ('[c2] "s"(c2), [bp16] "v"(bp16), [bp32] "v"(bp32), [n] "s"(n), [step] "s"(step), '
                '[vbase] "s"(nl.vb), [kbase] "s"(nl.kb), [sel_lo] "s"(sel_lo), [sel_hi] "s"(sel_hi)')
         for nt in (True, False):
             if tiles == 2 and not nt:

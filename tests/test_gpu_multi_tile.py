@@ -136,3 +136,20 @@ def test_partial_rows_are_the_micro_attention_triples(Hq, Hkv, n):
     np.testing.assert_allclose(pe[live] * adj, e[live], rtol=2e-4)
     num = np.linalg.norm(po[live] * adj[:, None] - MA[live], axis=1)
     assert np.all(num <= 1e-3 * np.linalg.norm(MA[live], axis=1) + 1e-12)
+
+
+@pytest.mark.parametrize("T", [1024, 4096])
+@pytest.mark.parametrize("Hq,Hkv,n", [(8, 1, 4), (8, 1, 8), (8, 1, 16), (8, 2, 25)])
+def test_long_runs_of_full_chunks_end_where_a_column_stops_seeing(T, Hq, Hkv, n):
+    # Blocks of many chunks: one statement loops over a block's full, fully visible chunks.  The lengths put the
+    # end of what every column sees (L - n + 1) into the middle of a block, on a chunk boundary, one row before and
+    # one after it, and into the first chunk of a block; one request ends exactly with a block.
+    lens = [2 * T + 517, 3 * T + 32 * 5 + n - 1, 3 * T + 32 * 5 + n - 2, 3 * T + 32 * 5 + n, T + n + 3, 2 * T]
+    w = make(lens, Hq, Hkv, n, T, seed=T // 1024 + n)
+    print("case multi-tile long runs T=%d Hq=%d Hkv=%d n=%d" % (T, Hq, Hkv, n), flush=True)
+    ref_out, ref_lse = reference(w)
+    for bps in (0, 1):
+        desc, flags, fused, two = run(w, blocks_per_split=bps)
+        assert desc["head_tile"] in (32, 64, 128) and flags == 0
+        for (out, lse), what in ((fused, "fused"), (two, "two calls")):
+            assert_parity(out.reshape(ref_out.shape), lse.reshape(ref_lse.shape), ref_out, ref_lse, "bf16", "%s T=%d bps=%d" % (what, T, bps))

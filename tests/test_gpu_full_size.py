@@ -54,12 +54,14 @@ def test_full_size_sampled_outputs_match_oracle(name, n_pairs):
         assert np.max(np.abs(gl - ref_lse) / np.maximum(1.0, np.abs(ref_lse))) <= tol["lse"]
 
 
-@pytest.mark.parametrize("q_len", [4, 8, 16])
-def test_full_size_multi_query_sampled_outputs_match_oracle(q_len):
-    # c3_70b with several query tokens per request: 32, 64 and 128 columns per K/V read (the multi-tile kernel), at
-    # full size; a seeded sample of (request, query token, q-head) outputs
-    print("case full-size c3_70b q_len %d" % q_len, flush=True)
-    w = synth.make(synth.recipe("c3_70b"), DEV)
+@pytest.mark.parametrize("name,q_len,n_pairs", [("c3_70b", 4, 384), ("c3_70b", 8, 384), ("c3_70b", 16, 384),
+                                                 ("c4_2m", 4, 48), ("c5_mixed", 8, 384)])
+def test_full_size_multi_query_sampled_outputs_match_oracle(name, q_len, n_pairs):
+    # several query tokens per request: 32, 64 and 128 columns per K/V read (the multi-tile kernel), at full size:
+    # c3_70b, one request of 2M tokens cut into many splits, and the mixed lengths (many short items per workgroup);
+    # a seeded sample of (request, query token, q-head) outputs
+    print("case full-size %s q_len %d" % (name, q_len), flush=True)
+    w = synth.make(synth.recipe(name), DEV)
     gen = torch.Generator(device=DEV)
     gen.manual_seed(4242)
     q = torch.randn((w["B"], q_len, w["Hq"], 128), device=DEV, generator=gen).to(w["q"].dtype)
@@ -71,7 +73,7 @@ def test_full_size_multi_query_sampled_outputs_match_oracle(q_len):
     plan.close()
     rng = np.random.RandomState(7 + q_len)
     vh = w["Hq"] * q_len  # virtual heads: query token * Hq + q-head
-    pairs = np.array([[int(rng.randint(0, w["B"])), int(rng.randint(0, vh))] for _ in range(382)]
+    pairs = np.array([[int(rng.randint(0, w["B"])), int(rng.randint(0, vh))] for _ in range(n_pairs - 2)]
                      + [[0, 0], [w["B"] - 1, vh - 1]], dtype=np.int32)
     ref, ref_lse = oracle.attention(synth.as_numpy(q), synth.as_numpy(w["k_pool"]), synth.as_numpy(w["v_pool"]),
                                     w["block_table_host"], w["seq_lens_host"], w["T"], w["scale"], pairs=pairs, n_threads=16)

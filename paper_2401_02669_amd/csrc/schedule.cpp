@@ -20,7 +20,12 @@ constexpr int kGroupsPerCu = 1;          // persistent MicroAttention workgroups
 constexpr int64_t kMinRunTiles = 8;      // shortest run worth a workgroup: two tiles per wavefront
 constexpr int kWaveItemsMinPerRun = 32;  // splits per run from which a wavefront takes whole splits ...
 constexpr int kWaveItemsMaxTiles = 128;  // ... if a split holds no more than this many tiles on average
-constexpr int64_t kSplitCostTiles = 4;   // fixed cost of one split (look-up, merge, partial rows), in tiles
+
+// Fixed cost of one split, in tiles (what a workgroup would have read meanwhile): look-ups, the query rows, the first
+// chunk's latency, merge and result rows.  It grows with the columns a work item serves; measured on the mixed-length
+// workload (64 requests, 16 to 866 514 tokens), where the runs that collect the short requests otherwise end last:
+// 4 columns 4..12 alike, 16 and 32 columns best at 24..32, 64 columns at 48..64, 128 columns flat from 48 on.
+int64_t split_cost_tiles(int cols) { return cols <= 8 ? 4 : cols <= 32 ? 32 : 56; }
 }
 
 int64_t tiles_of(int64_t L, int32_t T)
@@ -73,6 +78,7 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
     const int q_len = p.q_len > 0 ? p.q_len : 1;
     const int G = (p.num_q_heads / p.num_kv_heads) * q_len;  // (query token, q-head) columns per kv-head
     const int64_t tpb = (T + kTileTokens - 1) / kTileTokens;
+    const int64_t split_cost = split_cost_tiles(G);
 
     // kernel family, head tile, workgroup size
     int kernel = tuning.kernel;
@@ -126,16 +132,16 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
         // whatever that costs in partial rows.
         ranges = std::max<int64_t>(1, std::min<int64_t>(ranges, total_tiles / kMinRunTiles));
         // equal-cost cut of the stream; a request costs its tiles plus a fixed amount per split
-        const double total_cost = (double)total_tiles + (double)kSplitCostTiles * B;
+        const double total_cost = (double)total_tiles + (double)split_cost * B;
         int64_t m = 1;          // next boundary to place
         double cost_before = 0; // cost of the requests before the current one
         for (int i = 0; i < B && m < ranges; ++i) {
             const int r = order[i];
-            const double cost_end = cost_before + kSplitCostTiles + s.ntiles[r];
+            const double cost_end = cost_before + split_cost + s.ntiles[r];
             while (m < ranges) {
                 const double x = total_cost * (double)m / (double)ranges;
                 if (x >= cost_end) break;
-                int64_t t = (int64_t)std::llround(x - cost_before - kSplitCostTiles);
+                int64_t t = (int64_t)std::llround(x - cost_before - split_cost);
                 t = std::max<int64_t>(0, std::min<int64_t>(t, s.ntiles[r]));
                 const int64_t prev = cuts[r].empty() ? 0 : cuts[r].back();
                 // keep splits at least one tile per wavefront long; a boundary that would fall too close
@@ -183,11 +189,11 @@ da_status make_schedule(const da_problem &p, const int32_t *seq_lens_host, const
     const int64_t E = (int64_t)s.entries.size();
     ranges = std::max<int64_t>(1, std::min<int64_t>(ranges, E));
     double total_cost = 0;
-    for (const SplitEntry &e : s.entries) total_cost += kSplitCostTiles + (e.t1 - e.t0);
+    for (const SplitEntry &e : s.entries) total_cost += split_cost + (e.t1 - e.t0);
     s.range_start.assign(1, 0);
     double acc = 0;
     for (int64_t i = 0; i < E; ++i) {
-        const double c = kSplitCostTiles + (s.entries[i].t1 - s.entries[i].t0);
+        const double c = split_cost + (s.entries[i].t1 - s.entries[i].t0);
         const int64_t m = (int64_t)s.range_start.size();  // boundary being looked for
         // start a new run before entry i when the boundary lies nearer to its start than to its end,
         // while leaving at least one entry for every run still to come

@@ -351,7 +351,8 @@ def test_many_short_requests_one_wavefront_per_split(Hq, Hkv, dtype):
     out2, lse2 = plan.combine(po, pm, pe)
     torch.cuda.synchronize()
     assert plan.error_flags() == 0
-    assert max(plan.nsplits(r) for r in range(len(lens))) > 1 or Hq // Hkv > 16
+    # (a group of 16 columns and more costs a split so much that these plans leave every request whole)
+    assert max(plan.nsplits(r) for r in range(len(lens))) > 1 or Hq // Hkv >= 16
     plan.close()
     assert_parity(out.cpu().numpy(), lse.cpu().numpy(), ref_out, ref_lse, dtype, "wavefront splits, fused")
     assert_parity(out2.cpu().numpy(), lse2.cpu().numpy(), ref_out, ref_lse, dtype, "wavefront splits, two calls")

@@ -153,3 +153,23 @@ def test_schedule_of_a_large_batch_is_cheap_and_balanced():
     assert s["workgroups"] == 256
     assert s["max_workgroup_tokens"] <= 1.03 * float(lens.sum()) / 32 + 64
     assert sum(s["nsplits"]) <= 4096 + 31
+
+
+def test_a_wide_item_charges_a_split_more():
+    # Mixed lengths: the runs at the end of the reading order collect the short requests.  With many columns per
+    # item a split costs more (query rows, first-chunk latency, a wider merge), so those runs get fewer tokens and
+    # the runs of the long requests more: the largest run grows with the width, and the total is the same.
+    r = synth.recipe("c5_mixed")
+    lens = synth._lengths(r, np.random.RandomState(synth.BASE_SEED + r["index"]))
+    T = r["T"]
+    nb = (lens + T - 1) // T
+    worst = []
+    for q_len in (1, 4, 16):
+        p = problem(B=r["B"], Hq=r["Hq"], Hkv=r["Hkv"], T=T, max_blocks=int(nb.max()), num_phys=int(nb.sum()))
+        p.q_len = q_len
+        s = da.plan_schedule(p, lens, num_cus=256)
+        assert s["workgroups"] == 256 and sum(s["nsplits"]) <= r["B"] + 31
+        worst.append(s["max_workgroup_tokens"])
+    mean = float(lens.sum()) / 32
+    assert worst[0] <= 1.02 * mean + 64          # 4 columns: runs of (nearly) equal tokens
+    assert worst[0] < worst[1] < worst[2] <= 1.25 * mean

@@ -559,32 +559,46 @@ def emit():
     h.append("}")
     h.append("")
     for tiles in (2, 4):
-        ins = ["v_accvgpr_write_b32 a%d, 0" % r for r in list(range(0, 32 * tiles)) + [ESUM(t) + i for t in range(tiles) for i in range(4)]]
+        qregs = [QOP(t, s) + i for t in range(tiles) for s in range(4) for i in range(4)]
+        # the query rows asked for by load_q are there; a negative scale flips their signs (exact)
+        ins = ["s_waitcnt vmcnt(0)", "s_cmp_eq_u32 %[qsign], 0", "s_cbranch_scc1 1f"]
+        for r in qregs:
+            ins += ["v_accvgpr_read_b32 v%d, a%d" % (T(0), r), "v_xor_b32_e32 v%d, %%[qsign], v%d" % (T(0), T(0)),
+                    "v_accvgpr_write_b32 a%d, v%d" % (r, T(0))]
+        ins += ["1:"]
+        ins += ["v_accvgpr_write_b32 a%d, 0" % r for r in list(range(0, 32 * tiles)) + [ESUM(t) + i for t in range(tiles) for i in range(4)]]
         for t in range(tiles):
             ins += ["v_mov_b32_e32 v%d, 0xff800000" % M(t), "v_mov_b32_e32 v%d, 0xff800000" % MREF(t), "v_mov_b32_e32 v%d, 0" % NMU(t)]
-        h.append("// start of an item for %d tiles: accumulators and exp-sums := 0, maxima := -inf" % tiles)
-        h.append("__device__ __forceinline__ void begin_item_%d()" % tiles)
+        h.append("// start of an item for %d tiles: its query rows have arrived (qsign = 0x80008000 flips their signs, 0 leaves" % tiles)
+        h.append("// them); accumulators and exp-sums := 0, maxima := -inf")
+        h.append("__device__ __forceinline__ void begin_item_%d(uint32_t qsign)" % tiles)
         h.append("{")
         h.append("    asm volatile(")
         h.append(c_string(ins))
-        h.append("        ::: );")
+        h.append('        :: [qsign] "s"(qsign) : "scc", "memory");')
         h.append("}")
         h.append("")
-    h.append("// Q^T operand of tile t, k-step s (four registers)")
-    h.append("template <int t, int s>")
-    h.append("__device__ __forceinline__ void set_q(uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3)")
-    h.append("{")
-    first = True
-    for t in range(4):
-        for s in range(4):
-            q = QOP(t, s)
-            h.append("    %sif constexpr (t == %d && s == %d)" % ("" if first else "else ", t, s))
-            h.append('        asm volatile("v_accvgpr_write_b32 a%d, %%0\\n v_accvgpr_write_b32 a%d, %%1\\n v_accvgpr_write_b32 a%d, %%2\\n v_accvgpr_write_b32 a%d, %%3\\n"'
-                     % (q, q + 1, q + 2, q + 3))
-            h.append('                     "s_nop 1\\n" :: "v"(x0), "v"(x1), "v"(x2), "v"(x3));')
-            first = False
-    h.append("}")
-    h.append("")
+        # query rows straight into the accumulation registers
+        ins = ["v_accvgpr_write_b32 a%d, 0" % r for r in qregs]
+        ins += ["s_mov_b64 s[100:101], exec"]
+        for t in range(tiles):
+            ins += ["s_mov_b64 exec, %%[live%d]" % t]
+            ins += ["global_load_dwordx4 %s, %%[row%d], off%s" % (a4(QOP(t, s)), t, (" offset:%d" % (64 * s)) if s else "") for s in range(4)]
+        ins += ["s_mov_b64 exec, s[100:101]"]
+        h.append("// Q^T operands of an item's %d tiles: the lane's column reads bytes [64 s, +16) from `row` on for k-step s (the" % tiles)
+        h.append("// lane group's slice is part of the address); lanes outside `live` get zeros.  The loads are waited for by")
+        h.append("// begin_item_%d, not here." % tiles)
+        rows = ", ".join("const void *row%d" % t for t in range(tiles))
+        lives = ", ".join("uint64_t live%d" % t for t in range(tiles))
+        h.append("__device__ __forceinline__ void load_q_%d(%s, %s)" % (tiles, rows, lives))
+        h.append("{")
+        h.append("    asm volatile(")
+        h.append(c_string(ins))
+        h.append("        :: " + ", ".join('[row%d] "v"(row%d)' % (t, t) for t in range(tiles)) + ", "
+                 + ", ".join('[live%d] "s"(live%d)' % (t, t) for t in range(tiles)))
+        h.append('        : "s100", "s101", "memory");')
+        h.append("}")
+        h.append("")
     h.append("// accumulator of tile t, dimension group n (four registers)")
     h.append("template <int t, int n>")
     h.append("__device__ __forceinline__ void read_acc(float &x0, float &x1, float &x2, float &x3)")

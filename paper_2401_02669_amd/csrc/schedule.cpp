@@ -22,10 +22,11 @@ constexpr int kWaveItemsMinPerRun = 32;  // splits per run from which a wavefron
 constexpr int kWaveItemsMaxTiles = 128;  // ... if a split holds no more than this many tiles on average
 
 // Fixed cost of one split, in tiles (what a workgroup would have read meanwhile): look-ups, the query rows, the first
-// chunk's latency, merge and result rows.  It grows with the columns a work item serves; measured on the mixed-length
-// workload (64 requests, 16 to 866 514 tokens), where the runs that collect the short requests otherwise end last:
-// 4 columns 4..12 alike, 16 and 32 columns best at 24..32, 64 columns at 48..64, 128 columns flat from 48 on.
-int64_t split_cost_tiles(int cols) { return cols <= 8 ? 4 : cols <= 32 ? 32 : 56; }
+// chunk's latency, merge and result rows.  It grows with the columns a work item serves (an item of two 32-token
+// chunks takes a workgroup about 2 us at 4 columns, 6 us at 32, 9 us at 64, 12 us at 128); measured on the
+// mixed-length workload (64 requests, 16 to 866 514 tokens), where the runs that collect the short requests
+// otherwise end last: 4 columns 4..16 alike, 16 and 32 columns flat over 8..40, 64 and 128 columns best at 24..32.
+int64_t split_cost_tiles(int cols) { return cols <= 8 ? 4 : cols <= 32 ? 16 : 28; }
 }
 
 int64_t tiles_of(int64_t L, int32_t T)
